@@ -1,0 +1,115 @@
+/*
+ * iconv.h - C ABI of the implicit-im2col convolution library for AMD MI355X (gfx950).
+ *
+ * The operation is the 2-D convolution layer of the paper's section 2.1 (C_I input maps of
+ * H_I x W_I, a sliding H_F x W_F kernel, C_O output maps, batch N), evaluated as the GEMM
+ * that im2col lowering defines there (M = N*P*Q output pixels, N_gemm = K filters,
+ * K_gemm = C*R*S taps) with the lowered dimension ordered tap-row, tap-column, channel
+ * (channel fastest: the "channel-first" order of section 3.1) and formed on the fly inside
+ * each output tile's K loop (block-level channel-first im2col, section 5), so the lowered
+ * matrix never exists in device memory.
+ *
+ * Notation: N batch, H x W input map, C input channels, K filters, R x S filter, P x Q output
+ * map (the paper's N, H_I x W_I, C_I, C_O, H_F x W_F, H_O x W_O).
+ *
+ *   y[n,p,q,k] = sum_{r,s,c} x[n, p*stride + r*dilation - pad, q*stride + s*dilation - pad, c]
+ *                            * w[k,r,s,c]
+ *
+ * x is read as zero outside the map (symmetric zero padding), the filter is not flipped,
+ *   P = floor((H + 2*pad - dilation*(R-1) - 1) / stride) + 1,   Q alike with W and S.
+ *
+ * Layouts (dense, no strides):  x[((n*H+h)*W+w)*C+c]   (NHWC)
+ *                               w[((k*R+r)*S+s)*C+c]   (KRSC)
+ *                               y[((n*P+p)*Q+q)*K+k]   (NPQK, i.e. row-major M x K)
+ *
+ * Ownership and execution: every tensor pointer is a DEVICE pointer owned by the caller and
+ * must be 16-byte aligned.  x and w are only read; y is overwritten in full (no accumulate, no
+ * bias, one group).  The library allocates nothing, frees nothing and never synchronises: the
+ * kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream)
+ * and the results are valid once the caller has synchronised that stream.  Calls are
+ * thread-safe; there is no mutable global state.
+ *
+ * Errors are reported by the return value only (never abort, never throw):
+ */
+#ifndef ICONV_H
+#define ICONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ICONV_OK                 0
+#define ICONV_ERR_NULL          -1  /* a required pointer is NULL                               */
+#define ICONV_ERR_SHAPE         -2  /* a dimension <= 0, stride < 1, dilation < 1, pad < 0,
+                                       or an empty output (P < 1 or Q < 1)                      */
+#define ICONV_ERR_UNSUPPORTED   -3  /* unknown dtype/algo, or a tensor of 2^31 elements or more */
+#define ICONV_ERR_ALIGN         -4  /* a tensor pointer is not 16-byte aligned                  */
+#define ICONV_ERR_WORKSPACE     -5  /* explicit variant only: workspace missing or too small    */
+#define ICONV_ERR_LAUNCH        -6  /* the HIP runtime refused a launch                         */
+
+/* dtype: element type of x and w / of y.  Products and sums are always fp32. */
+#define ICONV_F32_F32    0  /* fp32 in, fp32 out (plain FMA path; correctness configuration)  */
+#define ICONV_BF16_F32   1  /* bf16 in, fp32 out (MFMA; the measured path)                    */
+#define ICONV_F16_F32    2  /* fp16 in, fp32 out (MFMA)                                       */
+#define ICONV_BF16_BF16  3  /* bf16 in, bf16 out (fp32 accumulators rounded to nearest even)  */
+#define ICONV_F16_F16    4  /* fp16 in, fp16 out                                              */
+
+/* algo, for iconv_workspace_bytes */
+#define ICONV_ALGO_IMPLICIT 0
+#define ICONV_ALGO_EXPLICIT 1
+
+/* Output map size for one spatial axis pair (formula above).  Host pointers P, Q.
+ * Returns ICONV_OK, ICONV_ERR_NULL or ICONV_ERR_SHAPE. */
+int iconv_out_shape(int H, int W, int R, int S, int stride, int pad, int dilation, int *P, int *Q);
+
+/* Implicit channel-first im2col convolution (paper sections 3 and 5).  Needs no workspace.
+ * Any C and K are accepted; C % 8 == 0 takes the MFMA path with 16-byte channel runs, C == 4
+ * takes the merged-tap path for low-channel first layers (the multi-tile idea of section 4.3),
+ * anything else (and ICONV_F32_F32) takes a plain direct kernel. */
+int iconv_fwd(const void *x_nhwc, const void *w_krsc, void *y_npqk,
+              int N, int H, int W, int C, int K, int R, int S,
+              int stride, int pad, int dilation, int dtype, void *stream);
+
+/* Device bytes the caller must provide as workspace.  ICONV_ALGO_IMPLICIT: always 0.
+ * ICONV_ALGO_EXPLICIT: the lowered matrix of section 2.1, M x (R*S*C) input elements.
+ * Returns 0 also for invalid arguments. */
+size_t iconv_workspace_bytes(int algo, int N, int H, int W, int C, int K, int R, int S,
+                             int stride, int pad, int dilation, int dtype);
+
+/* Explicit im2col followed by a GEMM (section 2.2): the comparison the paper argues against.
+ * Kernel 1 writes the lowered M x (R*S*C) matrix (columns in tap-row, tap-column, channel
+ * order) into `workspace`; kernel 2 multiplies it with the filter matrix using the same MFMA
+ * GEMM core (as a 1x1 convolution over the lowered matrix).  `workspace` is a device pointer,
+ * 16-byte aligned, of at least iconv_workspace_bytes(ICONV_ALGO_EXPLICIT, ...) bytes; its
+ * contents are overwritten.  Same result contract as iconv_fwd. */
+int iconv_fwd_explicit(const void *x_nhwc, const void *w_krsc, void *y_npqk,
+                       void *workspace, size_t workspace_bytes,
+                       int N, int H, int W, int C, int K, int R, int S,
+                       int stride, int pad, int dilation, int dtype, void *stream);
+
+/* Only the first half of the explicit variant (the lowering kernel), for timing it alone. */
+int iconv_im2col(const void *x_nhwc, void *workspace, size_t workspace_bytes,
+                 int N, int H, int W, int C, int R, int S,
+                 int stride, int pad, int dilation, int dtype, void *stream);
+
+/* Measurement helper: a plain device-to-device copy kernel of `bytes` bytes (multiple of 16,
+ * both pointers 16-byte aligned), used to calibrate memory-traffic counters and to measure
+ * the achievable copy bandwidth. */
+int iconv_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* Tile-selection override for sweeps: -1 (default) lets the library choose, other values pick
+ * entry `variant` of the kernel table (see iconv_variant_name).  Process-wide, not
+ * thread-safe; meant for benchmarking only.  Returns ICONV_ERR_UNSUPPORTED if out of range. */
+int iconv_set_variant(int variant);
+int iconv_num_variants(void);
+const char *iconv_variant_name(int variant);
+
+/* Static string for a status code. */
+const char *iconv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICONV_H */

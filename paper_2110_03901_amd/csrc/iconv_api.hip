@@ -1,0 +1,170 @@
+// C ABI of the library: argument checking, path selection, launches.  See include/iconv.h.
+#include <atomic>
+
+#include "iconv_common.h"
+
+using namespace iconv;
+
+namespace {
+
+std::atomic<int> g_variant{-1};
+
+int out_dim(int in, int filt, int stride, int pad, int dil) {
+    long span = (long)in + 2L * pad - (long)dil * (filt - 1) - 1;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+bool dtype_types(int dtype, int* in_t, int* out_t) {
+    switch (dtype) {
+        case ICONV_F32_F32:   *in_t = IN_F32;  *out_t = OUT_F32;  return true;
+        case ICONV_BF16_F32:  *in_t = IN_BF16; *out_t = OUT_F32;  return true;
+        case ICONV_F16_F32:   *in_t = IN_F16;  *out_t = OUT_F32;  return true;
+        case ICONV_BF16_BF16: *in_t = IN_BF16; *out_t = OUT_BF16; return true;
+        case ICONV_F16_F16:   *in_t = IN_F16;  *out_t = OUT_F16;  return true;
+        default: return false;
+    }
+}
+
+int in_bytes(int in_t) { return in_t == IN_F32 ? 4 : 2; }
+
+// Validates the shape arguments and fills `s`.  Returns an ICONV_* status.
+int make_shape(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dil, ConvShape* s) {
+    if (N < 1 || H < 1 || W < 1 || C < 1 || K < 1 || R < 1 || S < 1) return ICONV_ERR_SHAPE;
+    if (stride < 1 || dil < 1 || pad < 0) return ICONV_ERR_SHAPE;
+    const int P = out_dim(H, R, stride, pad, dil), Q = out_dim(W, S, stride, pad, dil);
+    if (P < 1 || Q < 1) return ICONV_ERR_SHAPE;
+    const long long lim = 1LL << 31;
+    const long long xe = (long long)N * H * W * C, we = (long long)K * R * S * C, ye = (long long)N * P * Q * K;
+    const long long le = (long long)N * P * Q * R * S * C;  // lowered matrix (explicit variant)
+    if (xe >= lim || we >= lim || ye >= lim) return ICONV_ERR_UNSUPPORTED;
+    // padded coordinates must stay inside int32 arithmetic as well
+    if ((long long)(H + 2LL * pad + (long long)dil * R) * (W + 2LL * pad + (long long)dil * S) * C >= lim * 4)
+        return ICONV_ERR_UNSUPPORTED;
+    (void)le;
+    s->N = N; s->H = H; s->W = W; s->C = C; s->K = K; s->R = R; s->S = S;
+    s->stride = stride; s->pad = pad; s->dil = dil; s->P = P; s->Q = Q;
+    s->PQ = P * Q; s->M = N * P * Q; s->Kg = C * R * S;
+    return ICONV_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int status_of(hipError_t e) { return e == hipSuccess ? ICONV_OK : ICONV_ERR_LAUNCH; }
+
+// Runs the convolution with the fastest kernel that accepts the shape.
+int run_conv(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t st) {
+    if (in_t != IN_F32 && (s.C % 8) == 0)
+        return status_of(launch_mfma(x, w, y, s, in_t, out_t, g_variant.load(), st));
+    return status_of(launch_direct(x, w, y, s, in_t, out_t, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+int iconv_out_shape(int H, int W, int R, int S, int stride, int pad, int dilation, int* P, int* Q) {
+    if (!P || !Q) return ICONV_ERR_NULL;
+    if (H < 1 || W < 1 || R < 1 || S < 1 || stride < 1 || dilation < 1 || pad < 0) return ICONV_ERR_SHAPE;
+    const int p = out_dim(H, R, stride, pad, dilation), q = out_dim(W, S, stride, pad, dilation);
+    if (p < 1 || q < 1) return ICONV_ERR_SHAPE;
+    *P = p; *Q = q;
+    return ICONV_OK;
+}
+
+int iconv_fwd(const void* x, const void* w, void* y, int N, int H, int W, int C, int K, int R, int S,
+              int stride, int pad, int dilation, int dtype, void* stream) {
+    if (!x || !w || !y) return ICONV_ERR_NULL;
+    ConvShape s;
+    int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s);
+    if (rc != ICONV_OK) return rc;
+    int in_t, out_t;
+    if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return ICONV_ERR_ALIGN;
+    return run_conv(x, w, y, s, in_t, out_t, (hipStream_t)stream);
+}
+
+size_t iconv_workspace_bytes(int algo, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                             int dilation, int dtype) {
+    ConvShape s;
+    int in_t, out_t;
+    if (algo != ICONV_ALGO_EXPLICIT) return 0;
+    if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK) return 0;
+    if (!dtype_types(dtype, &in_t, &out_t)) return 0;
+    return (size_t)s.M * (size_t)s.Kg * (size_t)in_bytes(in_t);
+}
+
+int iconv_im2col(const void* x, void* workspace, size_t workspace_bytes, int N, int H, int W, int C, int R, int S,
+                 int stride, int pad, int dilation, int dtype, void* stream) {
+    if (!x) return ICONV_ERR_NULL;
+    ConvShape s;
+    int rc = make_shape(N, H, W, C, 1, R, S, stride, pad, dilation, &s);
+    if (rc != ICONV_OK) return rc;
+    int in_t, out_t;
+    if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
+    const size_t need = (size_t)s.M * (size_t)s.Kg * (size_t)in_bytes(in_t);
+    if ((size_t)s.M * (size_t)s.Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < need) return ICONV_ERR_WORKSPACE;
+    if (!aligned16(x) || !aligned16(workspace)) return ICONV_ERR_ALIGN;
+    return status_of(launch_im2col(x, workspace, s, in_bytes(in_t), (hipStream_t)stream));
+}
+
+int iconv_fwd_explicit(const void* x, const void* w, void* y, void* workspace, size_t workspace_bytes, int N, int H,
+                       int W, int C, int K, int R, int S, int stride, int pad, int dilation, int dtype,
+                       void* stream) {
+    if (!x || !w || !y) return ICONV_ERR_NULL;
+    ConvShape s;
+    int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s);
+    if (rc != ICONV_OK) return rc;
+    int in_t, out_t;
+    if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
+    if ((size_t)s.M * (size_t)s.Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
+    const size_t need = (size_t)s.M * (size_t)s.Kg * (size_t)in_bytes(in_t);
+    if (!workspace || workspace_bytes < need) return ICONV_ERR_WORKSPACE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(workspace)) return ICONV_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_im2col(x, workspace, s, in_bytes(in_t), st);
+    if (e != hipSuccess) return ICONV_ERR_LAUNCH;
+    // The GEMM is a 1x1 stride-1 convolution over the lowered matrix seen as a 1 x 1 x M image
+    // with Kg channels; the KRSC filter tensor already is the K x Kg filter matrix in the same
+    // (tap-row, tap-column, channel) column order.
+    ConvShape g;
+    g.N = 1; g.H = 1; g.W = s.M; g.C = s.Kg; g.K = s.K; g.R = 1; g.S = 1;
+    g.stride = 1; g.pad = 0; g.dil = 1; g.P = 1; g.Q = s.M; g.PQ = s.M; g.M = s.M; g.Kg = s.Kg;
+    return run_conv(workspace, w, y, g, in_t, out_t, st);
+}
+
+int iconv_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src) return ICONV_ERR_NULL;
+    if (bytes == 0 || (bytes & 15u)) return ICONV_ERR_SHAPE;
+    if (!aligned16(dst) || !aligned16(src)) return ICONV_ERR_ALIGN;
+    return status_of(launch_copy(dst, src, bytes, (hipStream_t)stream));
+}
+
+int iconv_set_variant(int variant) {
+    if (variant < -1 || variant >= mfma_num_variants()) return ICONV_ERR_UNSUPPORTED;
+    g_variant.store(variant);
+    return ICONV_OK;
+}
+
+int iconv_num_variants(void) { return mfma_num_variants(); }
+
+const char* iconv_variant_name(int variant) {
+    if (variant < 0 || variant >= mfma_num_variants()) return "auto";
+    return mfma_variant_name(variant);
+}
+
+const char* iconv_status_string(int status) {
+    switch (status) {
+        case ICONV_OK: return "ok";
+        case ICONV_ERR_NULL: return "null pointer";
+        case ICONV_ERR_SHAPE: return "bad shape";
+        case ICONV_ERR_UNSUPPORTED: return "unsupported dtype, algo or tensor size";
+        case ICONV_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case ICONV_ERR_WORKSPACE: return "workspace missing or too small";
+        case ICONV_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

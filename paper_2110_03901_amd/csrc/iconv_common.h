@@ -1,0 +1,79 @@
+// Shared declarations of the iconv HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "iconv.h"
+
+namespace iconv {
+
+// Problem description handed to every kernel by value.  Notation as in iconv.h.
+struct ConvShape {
+    int N, H, W, C, K, R, S;
+    int stride, pad, dil;
+    int P, Q;
+    int M;       // N*P*Q   rows of the equivalent GEMM
+    int PQ;      // P*Q
+    int Kg;      // C*R*S   reduction length of the equivalent GEMM
+};
+
+typedef __bf16 bf16_t;
+typedef _Float16 f16_t;
+
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef f16_t f16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Element-type traits: storage type, MFMA fragment type and the 32x32x16 instruction.
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> {
+    typedef bf16x8 frag;
+    static __device__ __forceinline__ floatx16 mfma32(frag a, frag b, floatx16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Elem<f16_t> {
+    typedef f16x8 frag;
+    static __device__ __forceinline__ floatx16 mfma32(frag a, frag b, floatx16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
+
+// fp32 -> output element, round to nearest even.
+template <typename O> __device__ __forceinline__ O to_out(float v);
+template <> __device__ __forceinline__ float to_out<float>(float v) { return v; }
+template <> __device__ __forceinline__ f16_t to_out<f16_t>(float v) { return (f16_t)v; }
+template <> __device__ __forceinline__ bf16_t to_out<bf16_t>(float v) {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {          // NaN: keep it a NaN
+        u = (u >> 16) | 0x40u;
+    } else {
+        u = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;  // ties to even
+    }
+    uint16_t h = (uint16_t)u;
+    bf16_t r;
+    __builtin_memcpy(&r, &h, 2);
+    return r;
+}
+
+// ---- launchers implemented in the kernel translation units ---------------------------------
+// in/out element codes used by the launch tables
+enum InType { IN_F32 = 0, IN_BF16 = 1, IN_F16 = 2 };
+enum OutType { OUT_F32 = 0, OUT_BF16 = 1, OUT_F16 = 2 };
+
+hipError_t launch_direct(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
+                         hipStream_t stream);
+
+int mfma_num_variants();
+const char* mfma_variant_name(int v);
+// Picks a tile variant (or uses `variant` when >= 0) and launches the implicit-GEMM kernel.
+// Requires C % 8 == 0 and a 16-bit input type.
+hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
+                       int variant, hipStream_t stream);
+
+hipError_t launch_im2col(const void* x, void* lowered, const ConvShape& s, int elt_bytes, hipStream_t stream);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+}  // namespace iconv

@@ -1,0 +1,141 @@
+// Plain (non-MFMA) kernels: the direct convolution fallback, the explicit lowering kernel and
+// the copy probe.
+#include "iconv_common.h"
+
+namespace iconv {
+
+namespace {
+
+template <typename T> __device__ __forceinline__ float ld(const T* p) { return (float)*p; }
+
+// Direct convolution, one thread per output element, fp32 FMA in (r, s, c) order.
+// Lanes run along k, so x reads are wave-uniform broadcasts.  Used for fp32 inputs and for
+// channel counts the MFMA paths do not take; correctness path, not a fast one.
+template <typename TI, typename TO>
+__global__ void __launch_bounds__(256) direct_kernel(const TI* __restrict__ x, const TI* __restrict__ w,
+                                                    TO* __restrict__ y, ConvShape s) {
+    const long long total = (long long)s.M * s.K;
+    const long long stride_t = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride_t) {
+        const int k = (int)(idx % s.K);
+        const int m = (int)(idx / s.K);
+        const int n = m / s.PQ;
+        const int pq = m - n * s.PQ;
+        const int p = pq / s.Q, q = pq - p * s.Q;
+        const int h0 = p * s.stride - s.pad, w0 = q * s.stride - s.pad;
+        float acc = 0.f;
+        for (int r = 0; r < s.R; ++r) {
+            const int h = h0 + r * s.dil;
+            if ((unsigned)h >= (unsigned)s.H) continue;
+            for (int ss = 0; ss < s.S; ++ss) {
+                const int ww = w0 + ss * s.dil;
+                if ((unsigned)ww >= (unsigned)s.W) continue;
+                const TI* xp = x + ((size_t)((size_t)n * s.H + h) * s.W + ww) * s.C;
+                const TI* wp = w + ((size_t)((size_t)k * s.R + r) * s.S + ss) * s.C;
+                for (int c = 0; c < s.C; ++c) acc = fmaf(ld(xp + c), ld(wp + c), acc);
+            }
+        }
+        y[idx] = to_out<TO>(acc);
+    }
+}
+
+// Explicit im2col (paper section 2.1): lowered[m][(r*S+s)*C + c], zero where the tap falls
+// outside the map.  One thread per VEC consecutive channels of one (m, tap).
+template <typename V, int VEC>
+__global__ void __launch_bounds__(256) im2col_kernel(const V* __restrict__ x, V* __restrict__ low, ConvShape s) {
+    const int cv = s.C / VEC;                       // vectors per pixel
+    const long long total = (long long)s.M * s.R * s.S * cv;
+    const long long stride_t = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride_t) {
+        const int c = (int)(idx % cv);
+        long long t = idx / cv;
+        const int tap = (int)(t % (s.R * s.S));
+        const int m = (int)(t / (s.R * s.S));
+        const int r = tap / s.S, ss = tap - r * s.S;
+        const int n = m / s.PQ;
+        const int pq = m - n * s.PQ;
+        const int p = pq / s.Q, q = pq - p * s.Q;
+        const int h = p * s.stride - s.pad + r * s.dil, ww = q * s.stride - s.pad + ss * s.dil;
+        V v = {};
+        if ((unsigned)h < (unsigned)s.H && (unsigned)ww < (unsigned)s.W)
+            v = x[((size_t)((size_t)n * s.H + h) * s.W + ww) * cv + c];
+        low[idx] = v;
+    }
+}
+
+__global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride_t = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride_t) dst[i] = src[i];
+}
+
+int grid_for(long long total, int block) {
+    long long g = (total + block - 1) / block;
+    const long long cap = 256LL * 64;  // grid-stride beyond this
+    if (g > cap) g = cap;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+template <typename TI>
+hipError_t direct_out(const void* x, const void* w, void* y, const ConvShape& s, int out_t, hipStream_t st) {
+    const int grid = grid_for((long long)s.M * s.K, 256);
+    switch (out_t) {
+        case OUT_F32:
+            hipLaunchKernelGGL((direct_kernel<TI, float>), dim3(grid), dim3(256), 0, st, (const TI*)x, (const TI*)w,
+                               (float*)y, s);
+            break;
+        case OUT_BF16:
+            hipLaunchKernelGGL((direct_kernel<TI, bf16_t>), dim3(grid), dim3(256), 0, st, (const TI*)x, (const TI*)w,
+                               (bf16_t*)y, s);
+            break;
+        default:
+            hipLaunchKernelGGL((direct_kernel<TI, f16_t>), dim3(grid), dim3(256), 0, st, (const TI*)x, (const TI*)w,
+                               (f16_t*)y, s);
+            break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_direct(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
+                         hipStream_t st) {
+    switch (in_t) {
+        case IN_F32: return direct_out<float>(x, w, y, s, out_t, st);
+        case IN_BF16: return direct_out<bf16_t>(x, w, y, s, out_t, st);
+        default: return direct_out<f16_t>(x, w, y, s, out_t, st);
+    }
+}
+
+hipError_t launch_im2col(const void* x, void* low, const ConvShape& s, int elt_bytes, hipStream_t st) {
+    const int cbytes = s.C * elt_bytes;  // bytes of one pixel's channel run
+    if (cbytes % 16 == 0) {
+        const long long total = (long long)s.M * s.R * s.S * (cbytes / 16);
+        hipLaunchKernelGGL((im2col_kernel<uint4, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st, (const uint4*)x,
+                           (uint4*)low, ConvShape{s.N, s.H, s.W, cbytes / 16, s.K, s.R, s.S, s.stride, s.pad, s.dil,
+                                                  s.P, s.Q, s.M, s.PQ, s.Kg});
+    } else if (cbytes % 8 == 0) {
+        const long long total = (long long)s.M * s.R * s.S * (cbytes / 8);
+        hipLaunchKernelGGL((im2col_kernel<uint2, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st, (const uint2*)x,
+                           (uint2*)low, ConvShape{s.N, s.H, s.W, cbytes / 8, s.K, s.R, s.S, s.stride, s.pad, s.dil,
+                                                  s.P, s.Q, s.M, s.PQ, s.Kg});
+    } else if (elt_bytes == 4) {
+        const long long total = (long long)s.M * s.R * s.S * s.C;
+        hipLaunchKernelGGL((im2col_kernel<uint32_t, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st,
+                           (const uint32_t*)x, (uint32_t*)low, s);
+    } else {
+        const long long total = (long long)s.M * s.R * s.S * s.C;
+        hipLaunchKernelGGL((im2col_kernel<uint16_t, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st,
+                           (const uint16_t*)x, (uint16_t*)low, s);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(copy_kernel, dim3(grid_for((long long)n16, 256)), dim3(256), 0, st, (const uint4*)src,
+                       (uint4*)dst, n16);
+    return hipGetLastError();
+}
+
+}  // namespace iconv

@@ -1,0 +1,85 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the header
+declares, and its host-only entry points (shape, workspace size, status strings, argument
+validation that returns before any launch) behave as include/iconv.h states."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2110_03901_amd", "libiconv_mi355.so")
+HEADER = os.path.join(ROOT, "include", "iconv.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2110_03901_amd.build import build_library
+        build_library(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(iconv_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = declared_functions()
+    assert "iconv_fwd" in names and "iconv_fwd_explicit" in names and len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in iconv.h but not exported"
+
+
+def test_out_shape(lib):
+    P, Q = ctypes.c_int(), ctypes.c_int()
+    cases = [((56, 56, 3, 3, 1, 1, 1), (56, 56)), ((56, 56, 3, 3, 2, 1, 1), (28, 28)),
+             ((56, 56, 1, 1, 2, 0, 1), (28, 28)), ((64, 64, 3, 3, 1, 2, 2), (64, 64)),
+             ((224, 224, 7, 7, 2, 3, 1), (112, 112)), ((7, 7, 3, 3, 1, 1, 1), (7, 7)),
+             ((5, 5, 3, 3, 1, 0, 1), (3, 3)), ((5, 5, 3, 3, 2, 0, 1), (2, 2)), ((9, 4, 3, 2, 3, 1, 2), (3, 2))]
+    for args, want in cases:
+        assert lib.iconv_out_shape(*args, ctypes.byref(P), ctypes.byref(Q)) == 0
+        assert (P.value, Q.value) == want
+    assert lib.iconv_out_shape(2, 2, 3, 3, 1, 0, 1, ctypes.byref(P), ctypes.byref(Q)) == -2
+    assert lib.iconv_out_shape(8, 8, 3, 3, 0, 0, 1, ctypes.byref(P), ctypes.byref(Q)) == -2
+    assert lib.iconv_out_shape(8, 8, 3, 3, 1, 0, 1, None, ctypes.byref(Q)) == -1
+
+
+def test_workspace_bytes(lib):
+    lib.iconv_workspace_bytes.restype = ctypes.c_size_t
+    import workloads
+    for L in workloads.LAYERS.values():
+        code = 0 if L.dtype == "f32" else 1
+        assert lib.iconv_workspace_bytes(0, *L.shape_args(), code) == 0          # implicit: none
+        assert lib.iconv_workspace_bytes(1, *L.shape_args(), code) == L.M * L.k_gemm * L.elt_bytes()
+    assert lib.iconv_workspace_bytes(1, 1, 2, 2, 1, 1, 3, 3, 1, 0, 1, 1) == 0    # invalid shape
+
+
+def test_validation_happens_before_any_launch(lib):
+    f = lib.iconv_fwd
+    f.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 11 + [ctypes.c_void_p]
+    ok = (1, 8, 8, 16, 16, 3, 3, 1, 1, 1)
+    a = 4096  # a non-null, 16-byte aligned fake address; never dereferenced on these paths
+    assert f(None, a, a, *ok, 1, None) == -1
+    assert f(a, a, None, *ok, 1, None) == -1
+    assert f(a, a, a, 1, 8, 8, 0, 16, 3, 3, 1, 1, 1, 1, None) == -2
+    assert f(a, a, a, 1, 2, 2, 16, 16, 3, 3, 1, 0, 1, 1, None) == -2     # empty output
+    assert f(a, a, a, 1, 8, 8, 16, 16, 3, 3, 1, -1, 1, 1, None) == -2
+    assert f(a, a, a, *ok, 9, None) == -3                                # unknown dtype
+    assert f(a, a, a, 4, 32768, 32768, 16, 16, 3, 3, 1, 1, 1, 1, None) == -3  # >= 2^31 elements
+    assert f(a + 8, a, a, *ok, 1, None) == -4
+    e = lib.iconv_fwd_explicit
+    e.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_size_t] + [ctypes.c_int] * 11 + [ctypes.c_void_p]
+    assert e(a, a, a, a, 16, *ok, 1, None) == -5
+    assert e(a, a, a, None, 1 << 30, *ok, 1, None) == -5
+
+
+def test_status_strings_and_variants(lib):
+    lib.iconv_status_string.restype = ctypes.c_char_p
+    seen = {lib.iconv_status_string(c) for c in range(0, -7, -1)}
+    assert len(seen) == 7 and lib.iconv_status_string(0) == b"ok"
+    lib.iconv_variant_name.restype = ctypes.c_char_p
+    n = lib.iconv_num_variants()
+    assert n >= 1 and len({lib.iconv_variant_name(i) for i in range(n)}) == n
+    assert lib.iconv_set_variant(n) == -3 and lib.iconv_set_variant(-1) == 0
