@@ -73,6 +73,13 @@ const char* mfma_variant_name(int v);
 hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
                        int variant, hipStream_t stream);
 
+// Patch-reuse kernels (channel chunk outer, tap inner; input patch resident in LDS).
+int patch_num_variants();
+const char* patch_variant_name(int v);
+bool patch_supported(const ConvShape& s, int v);
+hipError_t launch_patch(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
+                        hipStream_t stream);
+
 hipError_t launch_im2col(const void* x, void* lowered, const ConvShape& s, int elt_bytes, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 

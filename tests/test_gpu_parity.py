@@ -115,7 +115,10 @@ def test_small_shapes_fp32(B, case):
 def test_every_tile_variant(B):
     """Force each kernel-table entry on shapes with ragged tiles in M, K and C."""
     shapes = [workloads.small_layer("v_a", 2, 19, 21, 40, 136, 3, 3, 1, 1, 1, seed_id=810),
-              workloads.small_layer("v_b", 1, 33, 31, 64, 72, 3, 3, 2, 1, 2, seed_id=811)]
+              workloads.small_layer("v_b", 1, 33, 31, 64, 72, 3, 3, 2, 1, 2, seed_id=811),
+              workloads.small_layer("v_c", 2, 14, 15, 136, 72, 3, 3, 1, 1, 1, seed_id=812),   # 3 channel chunks
+              workloads.small_layer("v_d", 1, 70, 9, 128, 40, 5, 5, 1, 2, 1, seed_id=813),    # tall, 25 taps
+              workloads.small_layer("v_e", 3, 9, 9, 192, 64, 1, 1, 1, 0, 1, seed_id=814)]     # 1x1
     try:
         for v in range(B.iconv_num_variants()):
             B.iconv_set_variant(v)
