@@ -56,6 +56,7 @@ int status_of(hipError_t e) { return e == hipSuccess ? ICONV_OK : ICONV_ERR_LAUN
 int run_conv(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t st) {
     if (in_t != IN_F32 && (s.C % 8) == 0)
         return status_of(launch_mfma(x, w, y, s, in_t, out_t, g_variant.load(), st));
+    if (in_t != IN_F32 && stem_supported(s)) return status_of(launch_stem(x, w, y, s, in_t, out_t, st));
     return status_of(launch_direct(x, w, y, s, in_t, out_t, st));
 }
 

@@ -80,6 +80,11 @@ bool patch_supported(const ConvShape& s, int v);
 hipError_t launch_patch(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
                         hipStream_t stream);
 
+// Merged-tap kernel for C == 4 first layers (stride 2, dilation 1, even W, S + (pad & 1) <= 8).
+bool stem_supported(const ConvShape& s);
+hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
+                       hipStream_t stream);
+
 hipError_t launch_im2col(const void* x, void* lowered, const ConvShape& s, int elt_bytes, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 

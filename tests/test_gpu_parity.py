@@ -95,7 +95,11 @@ SMALL = [
     ("direct_c3", 2, 9, 10, 3, 5, 3, 3, 1, 1, 1),           # generic channel count: direct kernel
     ("direct_c20", 1, 8, 8, 20, 7, 3, 3, 2, 1, 1),
     ("stem_c4", 2, 31, 29, 4, 64, 7, 7, 2, 3, 1),           # low-channel first layer
-    ("stem_c4_k24", 1, 20, 22, 4, 24, 3, 3, 1, 1, 1),
+    ("stem_c4_k24", 1, 20, 22, 4, 24, 3, 3, 1, 1, 1),       # stride 1: not the merged-tap kernel
+    ("stem_c4_3x3s2", 3, 34, 38, 4, 40, 3, 3, 2, 1, 1),     # odd pad: the run starts one pixel early
+    ("stem_c4_5x5s2_p2", 1, 40, 64, 4, 64, 5, 5, 2, 2, 1),  # even pad, Q = 32
+    ("stem_c4_7x7_wide", 1, 18, 140, 4, 72, 7, 7, 2, 3, 1), # several column blocks, K = 72
+    ("stem_c4_odd_w", 1, 21, 21, 4, 16, 7, 7, 2, 3, 1),     # odd W: falls back
 ]
 
 
