@@ -106,6 +106,11 @@ int iconv_set_variant(int variant);
 int iconv_num_variants(void);
 const char *iconv_variant_name(int variant);
 
+/* Test and measurement hook for the persistent kernels: n > 0 caps the number of workgroups a
+ * launch uses (each then walks through more output tiles), 0 restores the default of filling
+ * the device.  Process-wide, not thread-safe.  Returns ICONV_ERR_UNSUPPORTED for n < 0. */
+int iconv_set_max_workgroups(int n);
+
 /* Static string for a status code. */
 const char *iconv_status_string(int status);
 

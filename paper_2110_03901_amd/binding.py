@@ -43,6 +43,8 @@ _lib.iconv_probe_copy.restype = _i
 _lib.iconv_probe_copy.argtypes = [_p, _p, _sz, _p]
 _lib.iconv_set_variant.restype = _i
 _lib.iconv_set_variant.argtypes = [_i]
+_lib.iconv_set_max_workgroups.restype = _i
+_lib.iconv_set_max_workgroups.argtypes = [_i]
 _lib.iconv_num_variants.restype = _i
 _lib.iconv_variant_name.restype = ctypes.c_char_p
 _lib.iconv_variant_name.argtypes = [_i]
@@ -50,7 +52,7 @@ _lib.iconv_status_string.restype = ctypes.c_char_p
 _lib.iconv_status_string.argtypes = [_i]
 
 EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
-           "iconv_probe_copy", "iconv_set_variant", "iconv_num_variants", "iconv_variant_name",
+           "iconv_probe_copy", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name",
            "iconv_status_string"]
 
 
@@ -133,6 +135,12 @@ def iconv_probe_copy(dst, src, nbytes, stream=None) -> None:
 
 def iconv_set_variant(variant: int) -> None:
     rc = _lib.iconv_set_variant(variant)
+    if rc != 0:
+        raise IconvError(rc)
+
+
+def iconv_set_max_workgroups(n: int) -> None:
+    rc = _lib.iconv_set_max_workgroups(n)
     if rc != 0:
         raise IconvError(rc)
 

@@ -148,6 +148,12 @@ int iconv_set_variant(int variant) {
     return ICONV_OK;
 }
 
+int iconv_set_max_workgroups(int n) {
+    if (n < 0) return ICONV_ERR_UNSUPPORTED;
+    patch_set_max_workgroups(n);
+    return ICONV_OK;
+}
+
 int iconv_num_variants(void) { return mfma_num_variants(); }
 
 const char* iconv_variant_name(int variant) {

@@ -74,6 +74,7 @@ hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s
                        int variant, hipStream_t stream);
 
 // Patch-reuse kernels (channel chunk outer, tap inner; input patch resident in LDS).
+void patch_set_max_workgroups(int n);   // 0 = one range of tiles per resident workgroup (default)
 int patch_num_variants();
 const char* patch_variant_name(int v);
 bool patch_supported(const ConvShape& s, int v);

@@ -60,4 +60,25 @@ template <> __device__ __forceinline__ void store4<f16_t>(f16_t* p, float a, flo
     *reinterpret_cast<f16x4*>(p) = v;
 }
 
+// Four consecutive fp32 results (one 16-byte staging piece) to a buffer, converted to the output
+// type; an offset at or past the end of the buffer drops the store.
+template <typename O> __device__ __forceinline__ void store_piece(u32x4 v, rsrc_t rsrc, uint32_t off);
+template <> __device__ __forceinline__ void store_piece<float>(u32x4 v, rsrc_t rsrc, uint32_t off) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)off, 0, 0);
+}
+template <> __device__ __forceinline__ void store_piece<bf16_t>(u32x4 v, rsrc_t rsrc, uint32_t off) {
+    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const floatx4 f = __builtin_bit_cast(floatx4, v);
+    const bf16x4 h = {to_out<bf16_t>(f[0]), to_out<bf16_t>(f[1]), to_out<bf16_t>(f[2]), to_out<bf16_t>(f[3])};
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, h), rsrc, (int)off, 0, 0);
+}
+template <> __device__ __forceinline__ void store_piece<f16_t>(u32x4 v, rsrc_t rsrc, uint32_t off) {
+    typedef f16_t f16x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const floatx4 f = __builtin_bit_cast(floatx4, v);
+    const f16x4 h = {(f16_t)f[0], (f16_t)f[1], (f16_t)f[2], (f16_t)f[3]};
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, h), rsrc, (int)off, 0, 0);
+}
+
 }  // namespace iconv

@@ -29,23 +29,58 @@ struct PatchGeom {
     int a_blocks;        // wave-wide patch loads per wave and channel chunk
     int dph, dpw;        // (WAVES*RPB) / PW and % PW: patch-pixel step between a lane's loads
     int patch_bytes;     // LDS bytes of one patch buffer (multiple of 1024)
-    int patch_bufs;      // 2 when the layer has several channel chunks (double buffer), else 1
+    int total_tiles;     // N * tiles_h * tiles_w * tiles_n
+    int tiles_per_wg;    // contiguous tiles per workgroup
     float inv_tw;        // 1 / TW
 };
 
 // Patch swizzle.  The patch is an array of 256-byte windows (all 64 LDS banks), each holding
 // PPW = 16/CPR pixels of CPR 16-byte chunks.  Chunk c of pixel pp has logical slot
-// (pp % PPW)*CPR + c in window pp / PPW and lives at physical slot  logical ^ (window & 15).
-// An MFMA operand read has its 16 consecutive lanes on 16 pixels that are `stride` apart, same
-// chunk: XOR-ing the window number into all four slot bits spreads those over the 16 slots for
-// stride 1 (at most one clash when the run starts on an odd pixel) and for stride 2.
+// (pp % PPW)*CPR + c in window pp / PPW and lives at physical slot  logical ^ (window & 15) for even strides,
+// (window & (CPR-1)) for odd strides: an MFMA operand read has its 16 consecutive lanes on 16
+// pixels that are `stride` apart, same chunk.  For an odd stride those pixels spread evenly over
+// the pixel-in-window positions, and XOR-ing the window number into the chunk bits alone makes
+// the 16 slots distinct; for an even stride they share few pixel-in-window positions, and the
+// window number has to be XOR-ed into all four slot bits.
 //
 // Wave roles.  The workgroup has WAVES_M*WAVES_N compute waves and NLD loader waves.  Loader waves
 // only issue the global -> LDS loads (their address arithmetic then overlaps the compute waves'
-// MFMAs instead of delaying them); compute waves only read LDS and issue MFMAs.  All waves meet
-// at one barrier per K step.
-template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD>
-__global__ void __launch_bounds__((WAVES_M * WAVES_N + NLD) * 64)
+// MFMAs instead of delaying them); compute waves only read LDS, issue MFMAs and store results.
+// All waves meet at one barrier per K step.
+//
+// Persistence.  A workgroup owns a contiguous range of output tiles and walks through them as
+// one sequence of phases (tile, channel chunk).  While a phase is computed the loader waves
+// bring in the patch of the next phase -- the next chunk of the same tile or the first chunk of
+// the next tile -- into the other patch buffer, and the filter ring simply runs on across tile
+// boundaries.
+//
+// Output.  With SS == 0 the compute waves store their accumulators themselves.  That stalls
+// them for as long as the memory system takes to accept a tile (the write of y is the largest
+// traffic of the low-channel layers), so with SS > 0 they only drop the finished tile into an
+// LDS staging buffer (fp32, 16-byte pieces, XOR-swizzled by pixel) and go on with the next tile,
+// while NSW store waves drain the staging buffer to y -- SS wave-wide 16-byte-per-lane stores
+// per K step, whole row pieces per 16 lanes -- during the steps of the next tile.  The drain of
+// a tile ends one step before that tile's last, so the barrier of the last step separates it
+// from the compute waves' next deposit; the last tile is drained after one extra barrier at the
+// end.  Store waves are separate from loader waves because a wave that counts outstanding loads
+// with s_waitcnt vmcnt must not have stores in flight as well: stores need not retire in order
+// with loads.
+struct TileCoord {
+    int n, p0, q0, k0;
+};
+
+template <int BN> __device__ __forceinline__ TileCoord decode_tile(int t, const PatchGeom& g) {
+    TileCoord c;
+    const int tile_n = t % g.tiles_n; t /= g.tiles_n;
+    const int tile_w = t % g.tiles_w; t /= g.tiles_w;
+    const int tile_h = t % g.tiles_h;
+    c.n = t / g.tiles_h;
+    c.p0 = tile_h * g.TH; c.q0 = tile_w * g.TW; c.k0 = tile_n * BN;
+    return c;
+}
+
+template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW>
+__global__ void __launch_bounds__((WAVES_M * WAVES_N + NLD + NSW) * 64)
 ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const PatchGeom g) {
     constexpr int WAVES_C = WAVES_M * WAVES_N;  // compute waves
     constexpr int CPR = CB / 8;                 // 16-byte chunks per pixel (or filter row) and channel chunk
@@ -58,31 +93,38 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     constexpr int BSTAGE_BYTES = BN * PIX_BYTES;
     static_assert(BN % (RPB * NLD) == 0 && B_IT >= 1, "filter tile must divide over the loader waves");
     static_assert(NLD % 4 == 0, "the patch loader needs a multiple of four loader waves");
+    constexpr int BM = WAVES_M * MI * 32;
+    constexpr int SPR = BN / 4;                 // 16-byte fp32 pieces per staging row (one output pixel)
+    constexpr int ST_ROWS = 64 / SPR;           // staging rows one wave-wide store covers
+    constexpr int ST_IT = SS > 0 ? BM / ST_ROWS / (NSW > 0 ? NSW : 1) : 0;   // wave-wide stores per store wave per tile
     static_assert((STB - 2) * B_IT + (STB - 1) * LA < 64, "too many loads in flight for vmcnt");
+    static_assert((SS == 0 && NSW == 0) || (SS > 0 && NSW > 0 && BM % (ST_ROWS * NSW) == 0 && SPR <= 64),
+                  "staging rows must divide over the store waves");
     typedef typename Elem<T>::frag frag_t;
 
-    extern __shared__ u32x4 lds[];   // [patch 0][patch 1 if needed][STB filter stages][1 KiB sink per loader wave]
+    // [patch 0][patch 1][STB filter stages][1 KiB sink per loader wave][staging BM x BN fp32 if SS > 0]
+    extern __shared__ u32x4 lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int tile_n = tile % g.tiles_n; tile /= g.tiles_n;
-    const int tile_w = tile % g.tiles_w; tile /= g.tiles_w;
-    const int tile_h = tile % g.tiles_h;
-    const int n = tile / g.tiles_h;
-    const int p0 = tile_h * g.TH, q0 = tile_w * g.TW, k0 = tile_n * BN;
-
+    const int wg = xcd_remap(blockIdx.x, gridDim.x);
+    const int t_begin = wg * g.tiles_per_wg;
+    const int t_end = min(t_begin + g.tiles_per_wg, g.total_tiles);
     const int RS = s.R * s.S;
     const int chunks = (s.C + CB - 1) / CB;
-    const int steps = chunks * RS;
-    const uint32_t bstage_off = (uint32_t)(g.patch_bufs * g.patch_bytes);   // byte offset of the filter ring
+    const int phases = (t_end - t_begin) * chunks;           // (tile, channel chunk) pairs of this workgroup
+    const int steps = phases * RS;
+    const uint32_t bstage_off = 2u * (uint32_t)g.patch_bytes;   // byte offset of the filter ring
+    const uint32_t staging_off = bstage_off + STB * BSTAGE_BYTES + NLD * 1024;   // byte offset of the staging buffer
+    const int steps_per_tile = chunks * RS;
+    // which bits of the window number the patch swizzle XORs into the slot number (see above)
+    const int wmask = (s.stride & 1) ? (CPR - 1) : 15;
 
-    if (wave >= WAVES_C) {
+    if (wave >= WAVES_C && wave < WAVES_C + NLD) {
         // =========================== loader waves ===========================================
         const int lw = wave - WAVES_C;
-        const int h_base = p0 * s.stride - s.pad, w_base = q0 * s.stride - s.pad;
         const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * s.C * 2u;
         const uint32_t w_bytes = (uint32_t)s.K * s.Kg * 2u;
         const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
@@ -97,21 +139,34 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         // so the lane's pixel-in-window and chunk, unchanged: the lane's pixel moves by NLD*RPB, and
         // its (row, column) in the patch is advanced incrementally.
         const int a_win0 = lw * 4 + (lane >> 4);
-        const int a_slot = (lane & 15) ^ (a_win0 & 15);
+        const int a_slot = (lane & 15) ^ (a_win0 & wmask);
         const int a_lc = (a_slot % CPR) * 8;    // first channel (within a chunk) this lane fetches
         const int a_pp0 = a_win0 * PPW + a_slot / CPR;
         const int a_ph0 = a_pp0 / g.PW;
         const int a_pw0 = a_pp0 - a_ph0 * g.PW;
-        int a_ph, a_pw, a_j;                    // running state within one channel chunk
-        auto patch_reset = [&]() { a_ph = a_ph0; a_pw = a_pw0; a_j = 0; };
-        // one patch load of channel chunk `c0` into patch buffer `buf` (or a no-op load into the sink)
-        auto patch_load = [&](int buf, int c0, bool live) {
-            const int h = h_base + a_ph, ww = w_base + a_pw;
-            const bool real = live && a_j < g.a_blocks;          // wave-uniform
+        int a_ph, a_pw, a_j;                    // running state within one phase
+        int a_n = 0, a_hb = 0, a_wb = 0, a_c0 = 0, a_buf = 0;   // phase being loaded: image, patch origin, chunk, buffer
+        bool a_live = false;
+        auto patch_begin = [&](int phase) {     // point the patch loader at phase `phase` (or switch it off)
+            a_ph = a_ph0; a_pw = a_pw0; a_j = 0;
+            a_live = phase < phases;
+            if (a_live) {
+                const TileCoord tc = decode_tile<BN>(t_begin + phase / chunks, g);
+                a_n = tc.n;
+                a_hb = tc.p0 * s.stride - s.pad;
+                a_wb = tc.q0 * s.stride - s.pad;
+                a_c0 = (phase % chunks) * CB;
+                a_buf = phase & 1;
+            }
+        };
+        // one patch load (or a no-op load into the sink once the phase's patch is complete)
+        auto patch_load = [&](bool allowed) {
+            const int h = a_hb + a_ph, ww = a_wb + a_pw;
+            const bool real = allowed && a_live && a_j < g.a_blocks;   // wave-uniform
             const bool ok = real & (a_ph < g.PH) & ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W) &
-                            ((c0 + a_lc) < s.C);
-            const uint32_t off = (uint32_t)(((n * s.H + h) * s.W + ww) * s.C + c0 + a_lc) * 2u;
-            const uint32_t dst = real ? lds_base + (uint32_t)buf * g.patch_bytes + (uint32_t)(lw + a_j * NLD) * 1024u : sink;
+                            ((a_c0 + a_lc) < s.C);
+            const uint32_t off = (uint32_t)(((a_n * s.H + h) * s.W + ww) * s.C + a_c0 + a_lc) * 2u;
+            const uint32_t dst = real ? lds_base + (uint32_t)a_buf * g.patch_bytes + (uint32_t)(lw + a_j * NLD) * 1024u : sink;
             dma16(x_rsrc, ok ? off : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
             a_pw += g.dpw;
             const int wrap = a_pw >= g.PW ? 1 : 0;
@@ -122,16 +177,20 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 
         // ---- filter-tile loads (one BN x CB tile per step)
         const int pc = lane % CPR, lr = lane / CPR;
+        const bool ragged_c = (s.C % CB) != 0;
         uint32_t b_off[B_IT];
         bool b_ok[B_IT];
+        int b_tile = t_begin;                   // tile whose filters the next load belongs to
+        auto filter_tile = [&]() {
+            const TileCoord tc = decode_tile<BN>(b_tile, g);
 #pragma unroll
-        for (int j = 0; j < B_IT; ++j) {
-            const int row = (lw + j * NLD) * RPB + lr;
-            const int ch = swz<CPR>(row, pc) * 8;
-            b_ok[j] = (k0 + row) < s.K;
-            b_off[j] = (uint32_t)((k0 + row) * s.Kg + ch) * 2u;
-        }
-        const bool ragged_c = (s.C % CB) != 0;
+            for (int j = 0; j < B_IT; ++j) {
+                const int row = (lw + j * NLD) * RPB + lr;
+                b_ok[j] = (tc.k0 + row) < s.K;
+                b_off[j] = (uint32_t)((tc.k0 + row) * s.Kg + swz<CPR>(row, pc) * 8) * 2u;
+            }
+        };
+        filter_tile();
         int lr_ = 0, ls_ = 0, lc0 = 0;          // tap (lr_, ls_) of channel chunk lc0 to load next
         auto filter_load = [&](int stage, bool live) {
             const uint32_t delta = (uint32_t)((lr_ * s.S + ls_) * s.C + lc0) * 2u;
@@ -147,17 +206,23 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             }
             if (++ls_ == s.S) {
                 ls_ = 0;
-                if (++lr_ == s.R) { lr_ = 0; lc0 += CB; }
+                if (++lr_ == s.R) {
+                    lr_ = 0;
+                    lc0 += CB;
+                    if (lc0 >= s.C) {           // next tile
+                        lc0 = 0;
+                        if (++b_tile < t_end) filter_tile();
+                    }
+                }
             }
         };
 
-        // prologue: the whole patch of chunk 0, then what the STB-1 steps before the first one would
+        // prologue: the whole patch of phase 0, then what the STB-1 steps before the first one would
         // have issued (their filter tiles; no-op loads in place of patch slices), so that the
         // steady-state wait count holds from the first step on.  Loads complete in issue order, so
         // the first step's wait for its filter tile also covers the patch.
-        patch_reset();
-        for (int j = 0; j < g.a_blocks; ++j) patch_load(0, 0, true);
-        patch_reset();
+        patch_begin(0);
+        for (int j = 0; j < g.a_blocks; ++j) patch_load(true);
 #pragma unroll
         for (int j = 0; j < STB - 1; ++j) {
             filter_load(j, j < steps);
@@ -165,24 +230,72 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             for (int l = 0; l < LA; ++l) dma16(x_rsrc, x_bytes, sink);
         }
         int fill = STB - 1, step = 0;
-        for (int ck = 0; ck < chunks; ++ck) {
-            const bool next_chunk = ck + 1 < chunks;
+        for (int phase = 0; phase < phases; ++phase) {
+            patch_begin(phase + 1);
             for (int t = 0; t < RS; ++t, ++step) {
                 // Everything issued after this step's filter tile may stay in flight: STB-2 later
                 // filter tiles and STB-1 groups of patch loads.
                 wait_vmcnt<(STB - 2) * B_IT + (STB - 1) * LA>();
                 __syncthreads();
                 filter_load(fill, step + STB - 1 < steps);
-                // The next chunk's patch arrives LA loads per step; the last STB-1 steps of a chunk
-                // carry no-op loads only, so the patch is complete once the next chunk's first step
+                // The next phase's patch arrives LA loads per step; the last STB-1 steps of a phase
+                // carry no-op loads only, so the patch is complete once the next phase's first step
                 // has waited.
 #pragma unroll
-                for (int l = 0; l < LA; ++l) patch_load((ck + 1) & 1, (ck + 1) * CB, next_chunk && t <= RS - STB);
+                for (int l = 0; l < LA; ++l) patch_load(t <= RS - STB);
                 fill = fill + 1 == STB ? 0 : fill + 1;
             }
-            patch_reset();
         }
         wait_vmcnt<0>();
+        if (SS > 0) __syncthreads();            // the barrier that hands the last tile to the store waves
+        return;
+    }
+
+    if (SS > 0 && wave >= WAVES_C + NLD) {
+        // =========================== store waves ============================================
+        const int sw = wave - WAVES_C - NLD;
+        // Store number j of a tile (j = 0 .. ST_IT-1) covers staging rows (sw + j*NSW)*ST_ROWS .. +ST_ROWS,
+        // lane l: row +l/SPR, 16-byte piece l%SPR.
+        const uint32_t y_bytes = (uint32_t)s.M * (uint32_t)s.K * (uint32_t)sizeof(TO);   // < 2^32 checked by the host
+        const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, kRsrcFlags);
+        const int npx = g.TH * g.TW;
+        int d_tile = -1, d_j = ST_IT;           // tile being drained (-1: none), next store of it
+        TileCoord d_tc = {0, 0, 0, 0};
+        auto drain_begin = [&](int tile) {
+            d_tile = tile;
+            d_j = 0;
+            d_tc = decode_tile<BN>(tile, g);
+        };
+        auto drain_store = [&]() {              // one wave-wide store; lanes outside the tensor are dropped by the range check
+            if (d_tile < 0 || d_j >= ST_IT) return;              // wave-uniform: nothing left to drain
+            const bool real = true;
+            const int t = (sw + d_j * NSW) * ST_ROWS + lane / SPR;
+            const int c16 = lane % SPR;
+            const int th = (int)(((float)t + 0.5f) * g.inv_tw);
+            const int tw = t - th * g.TW;
+            const int p = d_tc.p0 + th, q = d_tc.q0 + tw;
+            const int col = d_tc.k0 + c16 * 4;
+            const bool ok = real & (t < npx) & (p < s.P) & (q < s.Q) & (col < s.K);
+            const u32x4 v = lds[(staging_off >> 4) + t * SPR + (c16 ^ (t & (SPR < 16 ? SPR - 1 : 15)))];
+            const uint32_t off = (uint32_t)(((d_tc.n * s.P + p) * s.Q + q) * s.K + col) * (uint32_t)sizeof(TO);
+            store_piece<TO>(v, y_rsrc, ok ? off : y_bytes);
+            ++d_j;
+        };
+
+        int tile = t_begin, tile_step = 0;
+        for (int step = 0; step < steps; ++step) {
+            __syncthreads();
+            if (tile_step == 0 && tile > t_begin) drain_begin(tile - 1);     // deposited before this barrier
+            // the previous tile leaves LDS SS stores per step, none in a tile's last step
+            if (tile_step < steps_per_tile - 1) {
+#pragma unroll
+                for (int l = 0; l < SS; ++l) drain_store();
+            }
+            if (++tile_step == steps_per_tile) { tile_step = 0; ++tile; }
+        }
+        __syncthreads();                        // the last tile has been deposited
+        drain_begin(t_end - 1);
+        for (int j = 0; j < ST_IT; ++j) drain_store();
         return;
     }
 
@@ -191,12 +304,15 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.TH * g.TW;
     int a_base[MI];                             // patch pixel of each A-fragment row at tap (0, 0)
+    int o_th[MI], o_tw[MI];                     // the same row as (row, column) of the output block
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int t = (wave_m * MI + mi) * 32 + frow;
         const int th = (int)(((float)t + 0.5f) * g.inv_tw);
         const int tw = t - th * g.TW;
         a_base[mi] = t < npx ? (th * g.PW + tw) * s.stride : 0;
+        o_th[mi] = t < npx ? th : (1 << 20);    // rows past the block never pass the p < P test
+        o_tw[mi] = tw;
     }
     int b_idx[NI][KI];                          // filter-fragment positions within a stage (16-byte units)
 #pragma unroll
@@ -205,100 +321,121 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 #pragma unroll
         for (int kk = 0; kk < KI; ++kk) b_idx[ni][kk] = row * CPR + swz<CPR>(row, kk * 2 + fk);
     }
+    const bool vec_ok = (s.K & 3) == 0;
 
-    floatx16 acc[MI][NI];
+    int stage = 0, phase = 0;
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        floatx16 acc[MI][NI];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    int stage = 0;
-    for (int ck = 0; ck < chunks; ++ck) {
-        const uint32_t patch_cur = (uint32_t)(ck & 1) * (g.patch_bytes >> 4);   // in 16-byte units
-        int tap_r = 0, tap_s = 0;
-        for (int t = 0; t < RS; ++t) {
-            __syncthreads();                    // this step's filter tile (and patch) has landed
-            const int tap_off = (tap_r * g.PW + tap_s) * s.dil;
-            const u32x4* Bt = lds + ((bstage_off + stage * BSTAGE_BYTES) >> 4);
-            int a_win[MI], a_sx[MI];
+        for (int ck = 0; ck < chunks; ++ck, ++phase) {
+            const uint32_t patch_cur = (uint32_t)(phase & 1) * (g.patch_bytes >> 4);   // in 16-byte units
+            int tap_r = 0, tap_s = 0;
+            for (int t = 0; t < RS; ++t) {
+                __syncthreads();                // this step's filter tile (and patch) has landed
+                const int tap_off = (tap_r * g.PW + tap_s) * s.dil;
+                const u32x4* Bt = lds + ((bstage_off + stage * BSTAGE_BYTES) >> 4);
+                int a_win[MI], a_sx[MI];
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    const int pp = a_base[mi] + tap_off;
+                    a_win[mi] = patch_cur + (pp / PPW) * 16;          // 256-byte window of this pixel
+                    a_sx[mi] = ((pp % PPW) * CPR + fk) ^ ((pp / PPW) & wmask);
+                }
+                // operand fragments LDS -> registers and MFMAs, in KG groups of K slices: all reads of
+                // a group are issued before its first MFMA, and the next group's reads follow that
+                // group's MFMAs into the pipe
+                constexpr int KG = KI >= 4 ? 2 : 1;     // groups per step
+                constexpr int KPG = KI / KG;            // K slices per group
+#pragma unroll
+                for (int gk = 0; gk < KG; ++gk) {
+                    frag_t af[KPG][MI], bfr[KPG][NI];
+#pragma unroll
+                    for (int k2 = 0; k2 < KPG; ++k2) {
+                        const int kk = gk * KPG + k2;
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi)
+                            af[k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ (kk * 2))]);
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) bfr[k2][ni] = __builtin_bit_cast(frag_t, Bt[b_idx[ni][kk]]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int k2 = 0; k2 < KPG; ++k2)
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                            for (int ni = 0; ni < NI; ++ni)
+                                acc[mi][ni] = Elem<T>::mfma32(bfr[k2][ni], af[k2][mi], acc[mi][ni]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                stage = stage + 1 == STB ? 0 : stage + 1;
+                if (++tap_s == s.S) { tap_s = 0; ++tap_r; }
+            }
+        }
+
+        // ---- the tile's epilogue.  The filter fragment is the MFMA's row operand and the pixel
+        // fragment its column operand, so lane l holds block pixel 32*frag + l%32 and, in
+        // accumulator element v, filter 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block: four
+        // consecutive filters per group of four elements, stored as one 16-byte (fp32) or 8-byte
+        // (16-bit) piece of the pixel's y row.  The stores are not waited for.
+        if (SS > 0) {
+            // deposit: fp32 piece (pixel t, filters 4*c16 .. +3) at staging[t*SPR + (c16 ^ (t & 15))]
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                const int pp = a_base[mi] + tap_off;
-                a_win[mi] = patch_cur + (pp / PPW) * 16;              // 256-byte window of this pixel
-                a_sx[mi] = ((pp % PPW) * CPR + fk) ^ ((pp / PPW) & 15);
-            }
-            // operand fragments LDS -> registers and MFMAs, in KG groups of K slices: all reads of a
-            // group are issued before its first MFMA, and the next group's reads follow that group's
-            // MFMAs into the pipe
-            constexpr int KG = KI >= 4 ? 2 : 1;     // groups per step
-            constexpr int KPG = KI / KG;            // K slices per group
+                const int t = (wave_m * MI + mi) * 32 + frow;
 #pragma unroll
-            for (int gk = 0; gk < KG; ++gk) {
-                frag_t af[KPG][MI], bfr[KPG][NI];
+                for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int k2 = 0; k2 < KPG; ++k2) {
-                    const int kk = gk * KPG + k2;
-#pragma unroll
-                    for (int mi = 0; mi < MI; ++mi) af[k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ (kk * 2))]);
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) bfr[k2][ni] = __builtin_bit_cast(frag_t, Bt[b_idx[ni][kk]]);
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int c16 = (wave_n * NI + ni) * 8 + 2 * gq + fk;
+                        floatx4 v = {acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2], acc[mi][ni][4 * gq + 3]};
+                        lds[(staging_off >> 4) + t * SPR + (c16 ^ (t & (SPR < 16 ? SPR - 1 : 15)))] = __builtin_bit_cast(u32x4, v);
+                    }
                 }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int k2 = 0; k2 < KPG; ++k2)
-#pragma unroll
-                    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Elem<T>::mfma32(bfr[k2][ni], af[k2][mi], acc[mi][ni]);
-                __builtin_amdgcn_sched_barrier(0);
             }
-            stage = stage + 1 == STB ? 0 : stage + 1;
-            if (++tap_s == s.S) { tap_s = 0; ++tap_r; }
+            continue;
         }
-    }
-
-    // ---- epilogue.  The filter fragment is the MFMA's row operand and the pixel fragment its
-    // column operand, so lane l holds tile pixel 32*frag + l%32 and, in accumulator element v,
-    // filter 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block: four consecutive filters per group of
-    // four elements, stored as one 16-byte (fp32) or 8-byte (16-bit) piece of the pixel's y row.
-    const bool vec_ok = (s.K & 3) == 0;
+        const TileCoord tc = decode_tile<BN>(tile, g);
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        const int t = (wave_m * MI + mi) * 32 + frow;
-        const int th = (int)(((float)t + 0.5f) * g.inv_tw);
-        const int tw = t - th * g.TW;
-        const int p = p0 + th, q = q0 + tw;
-        if (t < npx && p < s.P && q < s.Q) {
-            TO* yrow = y + (size_t)((n * s.P + p) * s.Q + q) * s.K;
+        for (int mi = 0; mi < MI; ++mi) {
+            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
+            if (p < s.P && q < s.Q) {
+                TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
+                for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const int col = k0 + (wave_n * NI + ni) * 32 + 8 * gq + 4 * fk;
-                    if (vec_ok && col + 3 < s.K) {
-                        store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
-                                   acc[mi][ni][4 * gq + 3]);
-                    } else {
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int col = tc.k0 + (wave_n * NI + ni) * 32 + 8 * gq + 4 * fk;
+                        if (vec_ok && col + 3 < s.K) {
+                            store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
+                                       acc[mi][ni][4 * gq + 3]);
+                        } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
+                        }
                     }
                 }
             }
         }
     }
+    if (SS > 0) __syncthreads();                // hands the last tile to the loader waves
 }
 
 // ---- host side ------------------------------------------------------------------------------------
 
 struct PatchCfg {
     const char* name;
-    int cb, waves_m, waves_n, mi, ni, stb, la, nld;
+    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw;
     int bm() const { return waves_m * mi * 32; }
     int bn() const { return waves_n * ni * 32; }
-    int waves() const { return waves_m * waves_n + nld; }   // compute + loader waves
+    int waves() const { return waves_m * waves_n + nld + nsw; }   // compute + loader + store waves
 };
 
 constexpr int kLdsLimit = 160 * 1024;
@@ -307,9 +444,16 @@ constexpr int kLdsLimit = 160 * 1024;
 // work of all (padded) tiles plus the patch pixels that have to be brought into LDS.
 bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
     const int BM = c.bm();
+    if (c.ss > 0) {
+        // the staged epilogue stores through a 32-bit buffer descriptor, needs K % 4 == 0 for whole
+        // 16-byte pieces, and must get a tile out within the steps of the next one
+        const int chunks = (s.C + c.cb - 1) / c.cb;
+        const int st_it = BM / (64 / (c.bn() / 4)) / c.nsw;
+        if ((s.K & 3) != 0 || (double)s.M * s.K * 4.0 >= 4294967296.0) return false;
+        if ((long)c.ss * ((long)chunks * s.R * s.S - 1) < st_it) return false;
+    }
     const int rpb = 64 / (c.cb / 8);
     const int RS = s.R * s.S;
-    const int chunks = (s.C + c.cb - 1) / c.cb;
     double best = 1e300;
     bool found = false;
     for (int tw = 1; tw <= s.Q && tw <= BM; ++tw) {
@@ -322,11 +466,11 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
         const int per_pass = rpb * c.nld;
         const int a_blocks = (int)((npix + per_pass - 1) / per_pass);
         const long patch_bytes = (long)a_blocks * c.nld * 1024;
-        const int bufs = chunks > 1 ? 2 : 1;
-        const long lds = bufs * patch_bytes + (long)c.stb * c.bn() * c.cb * 2 + c.nld * 1024;
+        const long staging = c.ss > 0 ? (long)BM * c.bn() * 4 : 0;
+        const long lds = 2 * patch_bytes + (long)c.stb * c.bn() * c.cb * 2 + c.nld * 1024 + staging;
         if (lds > kLdsLimit) continue;
-        // a later chunk's patch must fit into the loads of the steps that may carry it
-        if (chunks > 1 && (long)c.la * (RS - c.stb + 1) < a_blocks) continue;
+        // the next phase's patch must fit into the loads of the steps that may carry it
+        if ((long)c.la * (RS - c.stb + 1) < a_blocks) continue;
         const long tiles = (long)((s.P + th - 1) / th) * ((s.Q + tw - 1) / tw);
         const double cost = (double)tiles * ((double)BM * RS + 4.0 * (double)npix);
         if (cost < best) {
@@ -338,47 +482,102 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
             g->a_blocks = a_blocks;
             g->dph = per_pass / pw; g->dpw = per_pass % pw;
             g->patch_bytes = (int)patch_bytes;
-            g->patch_bufs = bufs;
             g->inv_tw = 1.0f / (float)tw;
         }
     }
     return found;
 }
 
-template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD>
+std::atomic<int> g_max_workgroups{0};
+
+int device_cus() {
+    static std::atomic<int> cus{0};
+    int v = cus.load(std::memory_order_acquire);
+    if (v == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        cus.store(v, std::memory_order_release);
+    }
+    return v;
+}
+
+// Splits `total` tiles over workgroups: k resident workgroups per compute unit for k = 1..occ,
+// each owning ceil(total / (cus*k)) contiguous tiles; takes the k with the fewest tiles on the
+// busiest compute unit, the larger k on a tie (more independent workgroups to overlap).
+void split_tiles(long total, int cus, int occ, int* per_wg, int* nwg) {
+    long best_load = -1;
+    for (int k = 1; k <= occ; ++k) {
+        const long per = (total + (long)cus * k - 1) / ((long)cus * k);
+        const long n = (total + per - 1) / per;
+        const long load = per * ((n + cus - 1) / cus);
+        if (best_load < 0 || load <= best_load) {
+            best_load = load;
+            *per_wg = (int)per;
+            *nwg = (int)n;
+        }
+    }
+}
+
+template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW>
 hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     PatchGeom g;
     if (!plan_geometry(s, c, &g)) return hipErrorInvalidConfiguration;
-    const int lds_bytes = g.patch_bufs * g.patch_bytes + STB * c.bn() * CB * 2 + NLD * 1024;
-    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD>;
+    const int lds_bytes = 2 * g.patch_bytes + STB * c.bn() * CB * 2 + NLD * 1024 + (SS > 0 ? c.bm() * c.bn() * 4 : 0);
+    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW>;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
         if (e != hipSuccess) return e;
         raised.store(true, std::memory_order_release);
     }
-    const long grid = (long)s.N * g.tiles_h * g.tiles_w * g.tiles_n;
-    if (grid > 0x7fffffffL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(c.waves() * 64), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y,
-                       s, g);
+    const long total = (long)s.N * g.tiles_h * g.tiles_w * g.tiles_n;
+    if (total > 0x7fffffffL) return hipErrorInvalidConfiguration;
+    // resident workgroups per compute unit for this LDS size (cached per kernel and size)
+    static std::atomic<int> occ_lds{-1}, occ_val{1};
+    int occ = occ_val.load(std::memory_order_acquire);
+    if (occ_lds.load(std::memory_order_acquire) != lds_bytes) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, c.waves() * 64, (size_t)lds_bytes) != hipSuccess || nb < 1)
+            nb = 1;
+        occ = nb;
+        occ_val.store(nb, std::memory_order_release);
+        occ_lds.store(lds_bytes, std::memory_order_release);
+    }
+    int nwg = 1;
+    g.total_tiles = (int)total;
+    const int cap = g_max_workgroups.load(std::memory_order_relaxed);
+    if (cap > 0) {
+        split_tiles(total, cap, 1, &g.tiles_per_wg, &nwg);
+    } else {
+        split_tiles(total, device_cus(), occ, &g.tiles_per_wg, &nwg);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(c.waves() * 64), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y, s, g);
     return hipGetLastError();
 }
 
-//   name                               CB  WM WN MI NI STB LA NLD   (compute waves + loader waves)
-#define ICONV_PATCH_VARIANTS(X)                                          \
-    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4)           \
-    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4)           \
-    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4)          \
-    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4)          \
-    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4)          \
-    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4)           \
-    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4)           \
-    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4)            \
-    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4)           \
-    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4)          \
-    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4)
+//   name                                  CB  WM WN MI NI STB LA NLD SS NSW
+// (compute + loader [+ store] waves; SS > 0: output staged in LDS and drained by NSW store waves)
+#define ICONV_PATCH_VARIANTS(X)                                                \
+    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0)           \
+    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0)           \
+    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0)          \
+    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0)          \
+    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4, 0, 0)          \
+    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0)           \
+    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4, 0, 0)           \
+    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0)            \
+    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0)           \
+    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4, 0, 0)          \
+    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0)        \
+    X(11, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2)        \
+    X(12, "p256x64_c64_w32x64_s3_8+4+2", 64, 8, 1, 1, 2, 3, 2, 4, 4, 2)        \
+    X(13, "p256x64_c64_w64x64_s3_4+4+2", 64, 4, 1, 2, 2, 3, 2, 4, 4, 2)        \
+    X(14, "p64x64_c64_w32x32_s3_4+4+2", 64, 2, 2, 1, 1, 3, 1, 4, 1, 2)         \
+    X(15, "p128x128_c64_w64x64_s3_4+4+2", 64, 2, 2, 2, 2, 3, 2, 4, 2, 2)       \
+    X(16, "p64x128_c64_w32x64_s3_4+4+2", 64, 2, 2, 1, 2, 3, 1, 4, 1, 2)
 
-#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld) {name, cb, wm, wn, mi, ni, stb, la, nld},
+#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw},
 const PatchCfg kPatchCfgs[] = {ICONV_PATCH_VARIANTS(X_CFG)};
 #undef X_CFG
 constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
@@ -386,8 +585,8 @@ constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
 template <typename T, typename TO>
 hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     switch (v) {
-#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld) \
-    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld>(kPatchCfgs[i], x, w, y, s, st);
+#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw) \
+    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw>(kPatchCfgs[i], x, w, y, s, st);
         ICONV_PATCH_VARIANTS(X_CASE)
 #undef X_CASE
         default: return hipErrorInvalidValue;
@@ -396,6 +595,7 @@ hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const Co
 
 }  // namespace
 
+void patch_set_max_workgroups(int n) { g_max_workgroups.store(n < 0 ? 0 : n); }
 int patch_num_variants() { return kNumPatch; }
 const char* patch_variant_name(int v) { return kPatchCfgs[v].name; }
 

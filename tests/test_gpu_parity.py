@@ -133,6 +133,56 @@ def test_every_tile_variant(B):
         B.iconv_set_variant(-1)
 
 
+def test_workgroups_walking_several_tiles(B):
+    """Cap the workgroup count so that every workgroup of the persistent kernels owns a range of
+    tiles: the patch of the next tile is prefetched while a tile computes, the filter ring runs
+    across tile boundaries and finished tiles are stored while the next one computes."""
+    shapes = [workloads.small_layer("w_a", 3, 20, 22, 64, 136, 3, 3, 1, 1, 1, seed_id=815),    # one chunk, 2 N tiles
+              workloads.small_layer("w_b", 2, 17, 19, 136, 72, 3, 3, 1, 1, 1, seed_id=816),    # three chunks
+              workloads.small_layer("w_c", 2, 24, 24, 72, 64, 5, 5, 1, 4, 2, seed_id=817)]     # dilated, ragged chunk
+    try:
+        for cap in (1, 2, 5):
+            B.iconv_set_max_workgroups(cap)
+            for v in [-1] + list(range(B.iconv_num_variants())):
+                if "p" != B.iconv_variant_name(v)[0] and v >= 0:
+                    continue
+                B.iconv_set_variant(v)
+                for L in shapes:
+                    print("cap", cap, "variant", B.iconv_variant_name(v), flush=True)
+                    check(B, L)
+    finally:
+        B.iconv_set_variant(-1)
+        B.iconv_set_max_workgroups(0)
+
+
+def test_staged_output_repeated_runs(B):
+    """Kernels that stage the output in LDS and drain it with separate store waves: many runs,
+    with and without several tiles per workgroup, must all match (a hand-off race between the
+    compute, loader and store waves would show up as an occasional wrong tile)."""
+    shapes = [workloads.small_layer("s_a", 1, 33, 31, 64, 72, 3, 3, 2, 1, 2, seed_id=818),
+              workloads.small_layer("s_b", 4, 28, 28, 64, 64, 3, 3, 1, 1, 1, seed_id=819),
+              workloads.small_layer("s_c", 2, 20, 22, 128, 64, 3, 3, 1, 1, 1, dtype="f16", seed_id=820)]
+    staged = [v for v in range(B.iconv_num_variants()) if B.iconv_variant_name(v).endswith("+2")]
+    assert staged
+    prepared = []
+    for L in shapes:
+        x, w = workloads.make_inputs(L)
+        prepared.append((L, x, w, conv_ref(x, w, L.stride, L.pad, L.dilation)))
+    try:
+        for v in staged:
+            B.iconv_set_variant(v)
+            for cap in (0, 3):
+                B.iconv_set_max_workgroups(cap)
+                for L, x, w, ref in prepared:
+                    for rep in range(6):
+                        err = rel_err(run_gpu(B, L, x, w, code_of(L)), ref)
+                        assert err <= TIGHT, (B.iconv_variant_name(v), cap, L.name, rep, err)
+            print("staged variant", B.iconv_variant_name(v), "ok", flush=True)
+    finally:
+        B.iconv_set_variant(-1)
+        B.iconv_set_max_workgroups(0)
+
+
 # ---- 16-bit outputs: correctly rounded accumulators ------------------------------------------
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
