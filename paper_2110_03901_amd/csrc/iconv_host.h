@@ -1,0 +1,43 @@
+// Host-side helpers shared by the launchers of the persistent kernels.
+#pragma once
+#include <atomic>
+
+#include "iconv_common.h"
+
+namespace iconv {
+
+// Number of compute units of the current device (cached).
+inline int device_cus() {
+    static std::atomic<int> cus{0};
+    int v = cus.load(std::memory_order_acquire);
+    if (v == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        cus.store(v, std::memory_order_release);
+    }
+    return v;
+}
+
+// Splits `total` tiles over workgroups: k resident workgroups per compute unit for k = 1..occ,
+// each owning ceil(total / (cus*k)) contiguous tiles; takes the k with the fewest tiles on the
+// busiest compute unit, the larger k on a tie (more independent workgroups to overlap).
+inline void split_tiles(long total, int cus, int occ, int* per_wg, int* nwg) {
+    long best_load = -1;
+    for (int k = 1; k <= occ; ++k) {
+        const long per = (total + (long)cus * k - 1) / ((long)cus * k);
+        const long n = (total + per - 1) / per;
+        const long load = per * ((n + cus - 1) / cus);
+        if (best_load < 0 || load <= best_load) {
+            best_load = load;
+            *per_wg = (int)per;
+            *nwg = (int)n;
+        }
+    }
+}
+
+// Cap on the number of workgroups of a persistent launch (0 = none); see iconv_set_max_workgroups.
+extern std::atomic<int> g_max_workgroups;
+
+}  // namespace iconv

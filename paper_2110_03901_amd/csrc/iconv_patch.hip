@@ -16,6 +16,7 @@
 
 #include "iconv_common.h"
 #include "iconv_device.h"
+#include "iconv_host.h"
 
 namespace iconv {
 
@@ -488,37 +489,6 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
     return found;
 }
 
-std::atomic<int> g_max_workgroups{0};
-
-int device_cus() {
-    static std::atomic<int> cus{0};
-    int v = cus.load(std::memory_order_acquire);
-    if (v == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-            v = 256;
-        cus.store(v, std::memory_order_release);
-    }
-    return v;
-}
-
-// Splits `total` tiles over workgroups: k resident workgroups per compute unit for k = 1..occ,
-// each owning ceil(total / (cus*k)) contiguous tiles; takes the k with the fewest tiles on the
-// busiest compute unit, the larger k on a tie (more independent workgroups to overlap).
-void split_tiles(long total, int cus, int occ, int* per_wg, int* nwg) {
-    long best_load = -1;
-    for (int k = 1; k <= occ; ++k) {
-        const long per = (total + (long)cus * k - 1) / ((long)cus * k);
-        const long n = (total + per - 1) / per;
-        const long load = per * ((n + cus - 1) / cus);
-        if (best_load < 0 || load <= best_load) {
-            best_load = load;
-            *per_wg = (int)per;
-            *nwg = (int)n;
-        }
-    }
-}
-
 template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW>
 hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     PatchGeom g;
@@ -595,6 +565,7 @@ hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const Co
 
 }  // namespace
 
+std::atomic<int> g_max_workgroups{0};
 void patch_set_max_workgroups(int n) { g_max_workgroups.store(n < 0 ? 0 : n); }
 int patch_num_variants() { return kNumPatch; }
 const char* patch_variant_name(int v) { return kPatchCfgs[v].name; }

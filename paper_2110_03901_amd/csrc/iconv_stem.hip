@@ -8,13 +8,16 @@
 // that the run starts on an even pixel and stays 16-byte aligned in LDS, and trailing pixels up
 // to eight.  Those extra positions carry zero weights and are zeroed on the input side as well.
 //
-// The input patch of a TH x TW output block and all weights of 64 filters stay in LDS for the
-// whole workgroup, so the only barrier is the one after the loads; the layer is bound by the
-// write of y, which the epilogue issues as 16-byte stores.
+// All weights of 64 filters stay in LDS for the whole (persistent) workgroup, which walks through a
+// contiguous range of TH x TW output blocks.  One loader wave brings the next block's input patch
+// into the other of two patch buffers while four compute waves run the current block's MFMAs and
+// store it; the only synchronisation is one barrier per block.  The layer is bound by the write
+// of y, which the epilogue issues as 16-byte stores.
 #include <atomic>
 
 #include "iconv_common.h"
 #include "iconv_device.h"
+#include "iconv_host.h"
 
 namespace iconv {
 
@@ -24,81 +27,113 @@ struct StemGeom {
     int TH, TW_LOG2;     // output block: TH rows, TW = 1 << TW_LOG2 (16 or 32) columns
     int PH, PPAIRS;      // patch rows, 16-byte pixel pairs per patch row
     int tiles_h, tiles_w, tiles_n;
+    int total_tiles, tiles_per_wg;
     int shift;           // 1 when pad is odd: the 8-pixel run starts one pixel left of tap 0
     int b_bytes;         // LDS bytes of the weights (R * 4 KiB)
+    int patch_bytes;     // LDS bytes of one patch buffer (whole wave-wide loads)
     float inv_ppairs;    // 1 / PPAIRS
 };
 
 constexpr int kStemBN = 64;
-constexpr int kStemWaves = 4;
+constexpr int kStemWaves = 4;        // compute waves; one more wave loads the patches
+
+struct StemTile {
+    int n, p0, q0, k0;
+};
+
+__device__ __forceinline__ StemTile stem_decode(int t, const StemGeom& g) {
+    StemTile c;
+    const int tile_n = t % g.tiles_n; t /= g.tiles_n;
+    const int tile_w = t % g.tiles_w; t /= g.tiles_w;
+    const int tile_h = t % g.tiles_h;
+    c.n = t / g.tiles_h;
+    c.p0 = tile_h * g.TH; c.q0 = tile_w << g.TW_LOG2; c.k0 = tile_n * kStemBN;
+    return c;
+}
 
 template <typename T, typename TO, int MI>
-__global__ void __launch_bounds__(kStemWaves * 64)
+__global__ void __launch_bounds__((kStemWaves + 1) * 64)
 stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const StemGeom g) {
     typedef typename Elem<T>::frag frag_t;
-    extern __shared__ u32x4 lds[];   // [weights: (r, k-chunk 0..3, filter 0..63) x 16 B][patch: (row, pixel pair) x 16 B]
+    // [weights: (r, k-chunk 0..3, filter 0..63) x 16 B][patch 0][patch 1], a patch = (row, pixel pair) x 16 B
+    extern __shared__ u32x4 lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int TW = 1 << g.TW_LOG2;
 
-    int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int tile_n = tile % g.tiles_n; tile /= g.tiles_n;
-    const int tile_w = tile % g.tiles_w; tile /= g.tiles_w;
-    const int tile_h = tile % g.tiles_h;
-    const int n = tile / g.tiles_h;
-    const int p0 = tile_h * g.TH, q0 = tile_w * TW, k0 = tile_n * kStemBN;
-    const int h_org = p0 * s.stride - s.pad;                 // input row of patch row 0
-    const int w_org = q0 * s.stride - s.pad - g.shift;       // input column of patch column 0 (even)
+    const int wg = xcd_remap(blockIdx.x, gridDim.x);
+    const int t_begin = wg * g.tiles_per_wg;
+    const int t_end = min(t_begin + g.tiles_per_wg, g.total_tiles);
+    // All tiles of a workgroup's range must use the same filters for the resident weights to be
+    // valid: the host only makes ranges that do (tiles_n == 1), or ranges of one tile.
+    const int k0 = stem_decode(t_begin, g).k0;
 
-    // ---- input patch: global -> LDS, one 16-byte pixel pair per lane.  A pair never straddles
-    // the image edge (W and w_org are even), so a pair is either loaded whole or zero.
-    {
-        const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * 8u;
-        const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
-        const uint32_t patch_base = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)lds + (uint32_t)g.b_bytes;
-        const int npairs = g.PH * g.PPAIRS;
-        for (int blk = wave; blk * 64 < npairs; blk += kStemWaves) {
-            const int pi = blk * 64 + lane;
-            const int ph = (int)(((float)pi + 0.5f) * g.inv_ppairs);
-            const int pj = pi - ph * g.PPAIRS;
-            const int h = h_org + ph, ww = w_org + 2 * pj;
-            const bool ok = (pi < npairs) & ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W);
-            const uint32_t off = (uint32_t)((n * s.H + h) * s.W + ww) * 8u;
-            dma16(x_rsrc, ok ? off : x_bytes, patch_base + (uint32_t)blk * 1024u);
-        }
-    }
-    // ---- weights: w[k][r][s][0..3] (8 bytes) -> slot (s + shift) of filter row r: 16-byte chunk
-    // (s + shift)/2, half (s + shift)%2; the other slots are zero.  Chunk-major so that the 32
-    // lanes of an operand read touch consecutive 16-byte words.
+    // ---- weights, once: w[k][r][s][0..3] (8 bytes) -> slot (s + shift) of filter row r: 16-byte
+    // chunk (s + shift)/2, half (s + shift)%2; the other slots are zero.  Chunk-major so that the
+    // 32 lanes of an operand read touch consecutive 16-byte words.
     {
         const uint2* w8 = reinterpret_cast<const uint2*>(w);
         uint2* b8 = reinterpret_cast<uint2*>(lds);
         const int items = kStemBN * s.R * 8;
-        for (int it = tid; it < items; it += kStemWaves * 64) {
-            const int j = it & 7;                 // slot within the 8-pixel run
-            const int kr = it >> 3;
-            const int r = kr % s.R, k = kr / s.R;
+        for (int it = tid; it < items; it += (kStemWaves + 1) * 64) {
+            const int k = it & (kStemBN - 1);     // filter fastest: neighbouring lanes write neighbouring words
+            const int rj = it / kStemBN;
+            const int j = rj & 7, r = rj >> 3;    // slot within the 8-pixel run, filter row
             const int ss = j - g.shift;
             uint2 v = {0u, 0u};
             if (ss >= 0 && ss < s.S && k0 + k < s.K) v = w8[((size_t)(k0 + k) * s.R + r) * s.S + ss];
             b8[(((r * 4 + (j >> 1)) * kStemBN + k) << 1) + (j & 1)] = v;
         }
     }
-    wait_vmcnt<0>();
-    __syncthreads();
 
-    // ---- MFMA loop over filter rows; no further synchronisation
+    if (wave == kStemWaves) {
+        // =========================== loader wave ============================================
+        // One 16-byte pixel pair per lane.  A pair never straddles the image edge (W and the patch
+        // origin column are even), so a pair is either loaded whole or zero.
+        const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * 8u;
+        const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
+        const uint32_t patch_base = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)lds + (uint32_t)g.b_bytes;
+        const int npairs = g.PH * g.PPAIRS;
+        auto load_patch = [&](int tile, int buf) {
+            const StemTile tc = stem_decode(tile, g);
+            const int h_org = tc.p0 * s.stride - s.pad;                 // input row of patch row 0
+            const int w_org = tc.q0 * s.stride - s.pad - g.shift;       // input column of patch column 0 (even)
+            for (int blk = 0; blk * 64 < npairs; ++blk) {
+                const int pi = blk * 64 + lane;
+                const int ph = (int)(((float)pi + 0.5f) * g.inv_ppairs);
+                const int pj = pi - ph * g.PPAIRS;
+                const int h = h_org + ph, ww = w_org + 2 * pj;
+                const bool ok = (pi < npairs) & ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W);
+                const uint32_t off = (uint32_t)((tc.n * s.H + h) * s.W + ww) * 8u;
+                dma16(x_rsrc, ok ? off : x_bytes, patch_base + (uint32_t)(buf * g.patch_bytes + blk * 1024));
+            }
+        };
+        load_patch(t_begin, 0);
+        wait_vmcnt<0>();
+        __syncthreads();                        // weights and patch 0 are in LDS
+        for (int tile = t_begin; tile < t_end; ++tile) {
+            // the buffer of tile+1 was last read for tile-1, which every compute wave finished
+            // before the barrier just passed
+            if (tile + 1 < t_end) load_patch(tile + 1, (tile + 1 - t_begin) & 1);
+            wait_vmcnt<0>();
+            __syncthreads();
+        }
+        return;
+    }
+
+    // =============================== compute waves ==============================================
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.TH * TW;
-    const u32x4* patch = lds + (g.b_bytes >> 4);
-    int a_idx[MI];                                 // pixel-pair index of the lane's run at filter row 0
+    int a_idx[MI], o_th[MI], o_tw[MI];            // pixel-pair index of the lane's run at filter row 0; block row/column
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int t = (wave * MI + mi) * 32 + frow;
         const int th = t >> g.TW_LOG2, tw = t & (TW - 1);
         a_idx[mi] = t < npx ? th * s.stride * g.PPAIRS + tw * (s.stride >> 1) + fk : fk;
+        o_th[mi] = t < npx ? th : (1 << 20);
+        o_tw[mi] = tw;
     }
     // which of the lane's two pixels per K slice are padding positions of the run
     bool zero_lo[2], zero_hi[2];
@@ -108,62 +143,66 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
         zero_lo[kk] = j < g.shift || j >= s.S + g.shift;
         zero_hi[kk] = (j + 1) < g.shift || (j + 1) >= s.S + g.shift;
     }
+    const bool vec_ok = (s.K & 3) == 0;
 
-    floatx16 acc[MI][2];
+    __syncthreads();                            // weights and patch 0 are in LDS
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        const u32x4* patch = lds + ((g.b_bytes + ((tile - t_begin) & 1) * g.patch_bytes) >> 4);
+        floatx16 acc[MI][2];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-    for (int r = 0; r < s.R; ++r) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            frag_t af[MI], bfr[2];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                u32x4 v = patch[a_idx[mi] + r * g.PPAIRS + 2 * kk];
-                if (zero_lo[kk]) { v.x = 0u; v.y = 0u; }
-                if (zero_hi[kk]) { v.z = 0u; v.w = 0u; }
-                af[mi] = __builtin_bit_cast(frag_t, v);
-            }
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
-                bfr[ni] = __builtin_bit_cast(frag_t, lds[(r * 4 + 2 * kk + fk) * kStemBN + ni * 32 + frow]);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Elem<T>::mfma32(bfr[ni], af[mi], acc[mi][ni]);
-        }
-    }
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    // ---- epilogue: lane l holds block pixel 32*frag + l%32 and, in accumulator element v, filter
-    // 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block (the filters are the MFMA's row operand).
-    const bool vec_ok = (s.K & 3) == 0;
+        for (int r = 0; r < s.R; ++r) {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        const int t = (wave * MI + mi) * 32 + frow;
-        const int th = t >> g.TW_LOG2, tw = t & (TW - 1);
-        const int p = p0 + th, q = q0 + tw;
-        if (t < npx && p < s.P && q < s.Q) {
-            TO* yrow = y + (size_t)((n * s.P + p) * s.Q + q) * s.K;
+            for (int kk = 0; kk < 2; ++kk) {
+                frag_t af[MI], bfr[2];
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
+                for (int mi = 0; mi < MI; ++mi) {
+                    u32x4 v = patch[a_idx[mi] + r * g.PPAIRS + 2 * kk];
+                    if (zero_lo[kk]) { v.x = 0u; v.y = 0u; }
+                    if (zero_hi[kk]) { v.z = 0u; v.w = 0u; }
+                    af[mi] = __builtin_bit_cast(frag_t, v);
+                }
 #pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const int col = k0 + ni * 32 + 8 * gq + 4 * fk;
-                    if (vec_ok && col + 3 < s.K) {
-                        store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
-                                   acc[mi][ni][4 * gq + 3]);
-                    } else {
+                for (int ni = 0; ni < 2; ++ni)
+                    bfr[ni] = __builtin_bit_cast(frag_t, lds[(r * 4 + 2 * kk + fk) * kStemBN + ni * 32 + frow]);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Elem<T>::mfma32(bfr[ni], af[mi], acc[mi][ni]);
+            }
+        }
+
+        // ---- epilogue: lane l holds block pixel 32*frag + l%32 and, in accumulator element v, filter
+        // 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block (the filters are the MFMA's row operand).
+        const StemTile tc = stem_decode(tile, g);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
+            if (p < s.P && q < s.Q) {
+                TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int col = k0 + ni * 32 + 8 * gq + 4 * fk;
+                        if (vec_ok && col + 3 < s.K) {
+                            store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
+                                       acc[mi][ni][4 * gq + 3]);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
+                        }
                     }
                 }
             }
         }
+        __syncthreads();                        // next patch has landed; this patch buffer may be refilled
     }
 }
 
@@ -184,21 +223,43 @@ bool plan_stem(const ConvShape& s, StemGeom* g) {
     const int ppairs = ((TW - 1) * s.stride + 8) / 2;
     const long patch_bytes = (((long)PH * ppairs + 63) / 64) * 1024;   // whole wave-wide loads
     const long b_bytes = (long)s.R * 4 * kStemBN * 16;
-    if (patch_bytes + b_bytes > kStemLdsLimit) return false;
+    if (2 * patch_bytes + b_bytes > kStemLdsLimit) return false;
     g->TH = TH; g->TW_LOG2 = tw_log2; g->PH = PH; g->PPAIRS = ppairs;
     g->tiles_h = (s.P + TH - 1) / TH; g->tiles_w = (s.Q + TW - 1) / TW; g->tiles_n = (s.K + kStemBN - 1) / kStemBN;
-    g->shift = shift; g->b_bytes = (int)b_bytes; g->inv_ppairs = 1.0f / (float)ppairs;
+    g->shift = shift; g->b_bytes = (int)b_bytes; g->patch_bytes = (int)patch_bytes; g->inv_ppairs = 1.0f / (float)ppairs;
+    const long total = (long)s.N * g->tiles_h * g->tiles_w * g->tiles_n;
+    if (total > 0x7fffffffL) return false;
+    g->total_tiles = (int)total;
+    g->tiles_per_wg = 1;
     return true;
 }
 
 template <typename T, typename TO>
-hipError_t launch_stem_t(const void* x, const void* w, void* y, const ConvShape& s, const StemGeom& g, hipStream_t st) {
-    const long patch_bytes = (((long)g.PH * g.PPAIRS + 63) / 64) * 1024;
-    const int lds_bytes = (int)(g.b_bytes + patch_bytes);
-    const long grid = (long)s.N * g.tiles_h * g.tiles_w * g.tiles_n;
-    if (grid > 0x7fffffffL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((stem_kernel<T, TO, kStemMI>), dim3((unsigned)grid), dim3(kStemWaves * 64), lds_bytes, st,
-                       (const T*)x, (const T*)w, (TO*)y, s, g);
+hipError_t launch_stem_t(const void* x, const void* w, void* y, const ConvShape& s, StemGeom g, hipStream_t st) {
+    const int lds_bytes = g.b_bytes + 2 * g.patch_bytes;
+    auto kern = stem_kernel<T, TO, kStemMI>;
+    const int threads = (kStemWaves + 1) * 64;
+    int nwg = g.total_tiles;
+    if (g.tiles_n == 1) {
+        // one filter tile: workgroups own ranges of blocks and keep the weights resident
+        static std::atomic<int> occ_lds{-1}, occ_val{1};
+        int occ = occ_val.load(std::memory_order_acquire);
+        if (occ_lds.load(std::memory_order_acquire) != lds_bytes) {
+            int nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, threads, (size_t)lds_bytes) != hipSuccess || nb < 1)
+                nb = 1;
+            occ = nb;
+            occ_val.store(nb, std::memory_order_release);
+            occ_lds.store(lds_bytes, std::memory_order_release);
+        }
+        // The kernel waits on memory most of the time, so every workgroup slot of the device is
+        // filled (as many resident workgroups per compute unit as fit), each with an equal range.
+        const int cap = g_max_workgroups.load(std::memory_order_relaxed);
+        const long slots = cap > 0 ? cap : (long)device_cus() * occ;
+        g.tiles_per_wg = (int)((g.total_tiles + slots - 1) / slots);
+        nwg = (g.total_tiles + g.tiles_per_wg - 1) / g.tiles_per_wg;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(threads), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y, s, g);
     return hipGetLastError();
 }
 

@@ -155,6 +155,24 @@ def test_workgroups_walking_several_tiles(B):
         B.iconv_set_max_workgroups(0)
 
 
+def test_merged_tap_workgroups_walking_several_blocks(B):
+    """The merged-tap kernel for 4-channel layers keeps its weights in LDS and double-buffers the
+    input patch over a range of output blocks: uncapped (few blocks per workgroup) and capped to
+    1, 2 and 3 workgroups (long ranges crossing rows and images, last range shorter)."""
+    shapes = [workloads.small_layer("m_a", 3, 70, 76, 4, 64, 7, 7, 2, 3, 1, seed_id=830),     # 16-wide blocks, odd pad
+              workloads.small_layer("m_b", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1, seed_id=831),    # 32-wide blocks, even pad
+              workloads.small_layer("m_c", 5, 24, 40, 4, 24, 3, 3, 2, 1, 1, dtype="f16", seed_id=832),
+              workloads.small_layer("m_d", 2, 30, 36, 4, 64, 7, 7, 2, 3, 1, seed_id=833)]
+    try:
+        for cap in (0, 1, 2, 3):
+            B.iconv_set_max_workgroups(cap)
+            for L in shapes:
+                print("cap", cap, L.name, flush=True)
+                check(B, L)
+    finally:
+        B.iconv_set_max_workgroups(0)
+
+
 def test_staged_output_repeated_runs(B):
     """Kernels that stage the output in LDS and drain it with separate store waves: many runs,
     with and without several tiles per workgroup, must all match (a hand-off race between the
