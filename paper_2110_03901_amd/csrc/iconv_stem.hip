@@ -9,10 +9,12 @@
 // to eight.  Those extra positions carry zero weights and are zeroed on the input side as well.
 //
 // All weights of 64 filters stay in LDS for the whole (persistent) workgroup, which walks through a
-// contiguous range of TH x TW output blocks.  One loader wave brings the next block's input patch
-// into the other of two patch buffers while four compute waves run the current block's MFMAs and
-// store it; the only synchronisation is one barrier per block.  The layer is bound by the write
-// of y, which the epilogue issues as 16-byte stores.
+// contiguous range of TH x TW output blocks.  The four waves read the next block's input patch
+// into registers before the current block's MFMAs and park it in the other of two LDS patch
+// buffers after the current block's stores; the only synchronisation is one barrier per block.
+// The layer is bound by the write of y, which goes through a wave-private LDS staging area so that
+// every store instruction covers whole cache lines.  Two workgroups of four waves share a compute
+// unit (two waves per SIMD), which leaves each wave 256 vector registers.
 #include <atomic>
 
 #include "iconv_common.h"
@@ -27,15 +29,17 @@ struct StemGeom {
     int TH, TW_LOG2;     // output block: TH rows, TW = 1 << TW_LOG2 (16 or 32) columns
     int PH, PPAIRS;      // patch rows, 16-byte pixel pairs per patch row
     int tiles_h, tiles_w, tiles_n;
-    int total_tiles, tiles_per_wg;
+    int total_tiles;
+    int tiles_base, tiles_rem;   // workgroup i owns tiles_base (+1 if i < tiles_rem) consecutive blocks
     int shift;           // 1 when pad is odd: the 8-pixel run starts one pixel left of tap 0
     int b_bytes;         // LDS bytes of the weights (R * 4 KiB)
-    int patch_bytes;     // LDS bytes of one patch buffer (whole wave-wide loads)
+    int patch_bytes;     // LDS bytes of one patch buffer (whole workgroup-wide pieces)
     float inv_ppairs;    // 1 / PPAIRS
 };
 
 constexpr int kStemBN = 64;
-constexpr int kStemWaves = 4;        // compute waves; one more wave loads the patches
+constexpr int kStemWaves = 4;
+constexpr int kStemPatchItems = 4;   // 16-byte patch pieces per lane at most (patch <= 16 KiB)
 
 struct StemTile {
     int n, p0, q0, k0;
@@ -52,10 +56,11 @@ __device__ __forceinline__ StemTile stem_decode(int t, const StemGeom& g) {
 }
 
 template <typename T, typename TO, int MI>
-__global__ void __launch_bounds__((kStemWaves + 1) * 64)
+__global__ void __launch_bounds__(kStemWaves * 64)
 stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const StemGeom g) {
     typedef typename Elem<T>::frag frag_t;
-    // [weights: (r, k-chunk 0..3, filter 0..63) x 16 B][patch 0][patch 1], a patch = (row, pixel pair) x 16 B
+    // [weights: (r, k-chunk 0..3, filter 0..63) x 16 B][patch 0][patch 1][output staging: 4 KiB per compute
+    // wave], a patch = (row, pixel pair) x 16 B
     extern __shared__ u32x4 lds[];
 
     const int tid = threadIdx.x;
@@ -64,78 +69,123 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     const int TW = 1 << g.TW_LOG2;
 
     const int wg = xcd_remap(blockIdx.x, gridDim.x);
-    const int t_begin = wg * g.tiles_per_wg;
-    const int t_end = min(t_begin + g.tiles_per_wg, g.total_tiles);
+    // ranges differ by at most one tile
+    const int t_begin = wg * g.tiles_base + min(wg, g.tiles_rem);
+    const int t_end = t_begin + g.tiles_base + (wg < g.tiles_rem ? 1 : 0);
     // All tiles of a workgroup's range must use the same filters for the resident weights to be
     // valid: the host only makes ranges that do (tiles_n == 1), or ranges of one tile.
     const int k0 = stem_decode(t_begin, g).k0;
 
-    // ---- weights, once: w[k][r][s][0..3] (8 bytes) -> slot (s + shift) of filter row r: 16-byte
-    // chunk (s + shift)/2, half (s + shift)%2; the other slots are zero.  Chunk-major so that the
-    // 32 lanes of an operand read touch consecutive 16-byte words.
-    {
-        const uint2* w8 = reinterpret_cast<const uint2*>(w);
-        uint2* b8 = reinterpret_cast<uint2*>(lds);
-        const int items = kStemBN * s.R * 8;
-        for (int it = tid; it < items; it += (kStemWaves + 1) * 64) {
-            const int k = it & (kStemBN - 1);     // filter fastest: neighbouring lanes write neighbouring words
-            const int rj = it / kStemBN;
-            const int j = rj & 7, r = rj >> 3;    // slot within the 8-pixel run, filter row
-            const int ss = j - g.shift;
-            uint2 v = {0u, 0u};
-            if (ss >= 0 && ss < s.S && k0 + k < s.K) v = w8[((size_t)(k0 + k) * s.R + r) * s.S + ss];
-            b8[(((r * 4 + (j >> 1)) * kStemBN + k) << 1) + (j & 1)] = v;
-        }
+    // ---- patch loads: lane-constant part.  Piece i of the lane is pixel pair (i * 256 + tid) of the
+    // patch in row-major (row, pair) order.  A pair never straddles the image edge (W and the patch
+    // origin column are even), so a pair is either loaded whole or zero.
+    const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * 8u;
+    const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
+    const int npairs = g.PH * g.PPAIRS;
+    int p_h[kStemPatchItems], p_w[kStemPatchItems];       // patch row and column (in pixels) of the piece; column << 0: none
+#pragma unroll
+    for (int i = 0; i < kStemPatchItems; ++i) {
+        const int pi = i * (kStemWaves * 64) + tid;
+        const int ph = (int)(((float)pi + 0.5f) * g.inv_ppairs);
+        p_h[i] = pi < npairs ? ph : 0;
+        p_w[i] = pi < npairs ? 2 * (pi - ph * g.PPAIRS) : -(1 << 30);
     }
-
-    if (wave == kStemWaves) {
-        // =========================== loader wave ============================================
-        // One 16-byte pixel pair per lane.  A pair never straddles the image edge (W and the patch
-        // origin column are even), so a pair is either loaded whole or zero.
-        const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * 8u;
-        const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
-        const uint32_t patch_base = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)lds + (uint32_t)g.b_bytes;
-        const int npairs = g.PH * g.PPAIRS;
-        auto load_patch = [&](int tile, int buf) {
-            const StemTile tc = stem_decode(tile, g);
-            const int h_org = tc.p0 * s.stride - s.pad;                 // input row of patch row 0
-            const int w_org = tc.q0 * s.stride - s.pad - g.shift;       // input column of patch column 0 (even)
-            for (int blk = 0; blk * 64 < npairs; ++blk) {
-                const int pi = blk * 64 + lane;
-                const int ph = (int)(((float)pi + 0.5f) * g.inv_ppairs);
-                const int pj = pi - ph * g.PPAIRS;
-                const int h = h_org + ph, ww = w_org + 2 * pj;
-                const bool ok = (pi < npairs) & ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W);
-                const uint32_t off = (uint32_t)((tc.n * s.H + h) * s.W + ww) * 8u;
-                dma16(x_rsrc, ok ? off : x_bytes, patch_base + (uint32_t)(buf * g.patch_bytes + blk * 1024));
+    auto load_patch = [&](int tile, u32x4 (&regs)[kStemPatchItems]) {
+        const StemTile tc = stem_decode(tile, g);
+        const int h_org = tc.p0 * s.stride - s.pad;                 // input row of patch row 0
+        const int w_org = tc.q0 * s.stride - s.pad - g.shift;       // input column of patch column 0 (even)
+        const int base = (tc.n * s.H + h_org) * s.W + w_org;        // may be negative; in-range sums are not
+#pragma unroll
+        for (int i = 0; i < kStemPatchItems; ++i) {
+            if (i * (kStemWaves * 64) < npairs) {                   // uniform
+                const int h = h_org + p_h[i], ww = w_org + p_w[i];
+                const bool ok = ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W);
+                const uint32_t off = (uint32_t)(base + p_h[i] * s.W + p_w[i]) * 8u;
+                regs[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, ok ? off : x_bytes, 0, 0));
             }
-        };
-        load_patch(t_begin, 0);
-        wait_vmcnt<0>();
-        __syncthreads();                        // weights and patch 0 are in LDS
-        for (int tile = t_begin; tile < t_end; ++tile) {
-            // the buffer of tile+1 was last read for tile-1, which every compute wave finished
-            // before the barrier just passed
-            if (tile + 1 < t_end) load_patch(tile + 1, (tile + 1 - t_begin) & 1);
-            wait_vmcnt<0>();
-            __syncthreads();
         }
-        return;
+    };
+    auto park_patch = [&](int buf, const u32x4 (&regs)[kStemPatchItems]) {
+        u32x4* dst = lds + ((g.b_bytes + buf * g.patch_bytes) >> 4) + tid;
+#pragma unroll
+        for (int i = 0; i < kStemPatchItems; ++i)
+            if (i * (kStemWaves * 64) < npairs) dst[i * (kStemWaves * 64)] = regs[i];
+    };
+    u32x4 pregs[kStemPatchItems];
+    load_patch(t_begin, pregs);                 // in flight while the weights are laid out
+
+    // ---- weights, once: w[k][r][s][0..3] (8 bytes) -> slot (s + shift) of filter row r: 16-byte
+    // chunk (s + shift)/2, half (s + shift)%2; the other slots are zero.  Chunk-major, so that the
+    // 32 lanes of an operand read touch consecutive 16-byte words; filter k of (r, chunk) sits at
+    // k ^ ((4r + chunk) & 15), which keeps those reads a permutation of consecutive words and
+    // spreads the tap writes below (consecutive lanes = consecutive taps of one filter, which
+    // would otherwise all fall into the same banks) over the banks.  Index arithmetic divides by
+    // multiplying with a reciprocal in fp32: (i + 0.5) / d is never closer than 0.5 / d to an
+    // integer, far more than the rounding error at these sizes (i < 2^13, d <= 80).
+    {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        uint2* b8 = reinterpret_cast<uint2*>(lds);
+        constexpr int nthreads = kStemWaves * 64;
+        // the padding slots of the 8-pixel runs (filter fastest)
+        const int npad = 8 - s.S;
+        const float inv_npad = npad > 0 ? 1.0f / (float)npad : 0.f;
+        for (int it = tid; it < kStemBN * s.R * npad; it += nthreads) {
+            const int k = it & (kStemBN - 1);
+            const int rj = it >> 6;
+            const int r = (int)(((float)rj + 0.5f) * inv_npad), jj = rj - r * npad;
+            const int j = jj < g.shift ? jj : jj + s.S;
+            const int rc = r * 4 + (j >> 1);
+            b8[((rc * kStemBN + (k ^ (rc & 15))) << 1) + (j & 1)] = uint2{0u, 0u};
+        }
+        // the taps, read in memory order (coalesced), sixteen loads in flight per thread; filters
+        // beyond K read as zero (offset past the end of the buffer)
+        const int RS = s.R * s.S;
+        const int items = kStemBN * RS;
+        const float inv_rs = 1.0f / (float)RS, inv_s = 1.0f / (float)s.S;
+        const uint32_t w_bytes = (uint32_t)s.K * RS * 8u;
+        const rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(w), 0, w_bytes, kRsrcFlags);
+        const uint32_t w_base = (uint32_t)k0 * RS * 8u;
+        for (int base = tid; base < items; base += nthreads * 16) {
+            u32x2 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int it = base + u * nthreads;
+                v[u] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(
+                                                     w_rsrc, it < items ? w_base + (uint32_t)it * 8u : w_bytes, 0, 0));
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int it = base + u * nthreads;
+                const int k = (int)(((float)it + 0.5f) * inv_rs);
+                const int rs = it - k * RS;
+                const int r = (int)(((float)rs + 0.5f) * inv_s), j = rs - r * s.S + g.shift;
+                const int rc = r * 4 + (j >> 1);
+                if (it < items) b8[((rc * kStemBN + (k ^ (rc & 15))) << 1) + (j & 1)] = uint2{v[u].x, v[u].y};
+            }
+        }
     }
 
-    // =============================== compute waves ==============================================
+    // ---- per-lane constants of the block loop
+    // Everything that depends only on the lane is computed once, so that a block costs few
+    // vector instructions besides its LDS reads, MFMAs and stores.
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.TH * TW;
-    int a_idx[MI], o_th[MI], o_tw[MI];            // pixel-pair index of the lane's run at filter row 0; block row/column
+    constexpr int BM = kStemWaves * MI * 32;
+    const char* lds_b = reinterpret_cast<const char*>(lds);
+    uint32_t a_off[MI];                           // byte offset in the patch of the lane's run at filter row 0
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int t = (wave * MI + mi) * 32 + frow;
         const int th = t >> g.TW_LOG2, tw = t & (TW - 1);
-        a_idx[mi] = t < npx ? th * s.stride * g.PPAIRS + tw * (s.stride >> 1) + fk : fk;
-        o_th[mi] = t < npx ? th : (1 << 20);
-        o_tw[mi] = tw;
+        a_off[mi] = (uint32_t)(t < npx ? th * s.stride * g.PPAIRS + tw * (s.stride >> 1) + fk : fk) * 16u;
     }
-    // which of the lane's two pixels per K slice are padding positions of the run
+    // weights of (r, kk, ni): chunk 2kk + fk, filter 32ni + frow at slot (frow ^ ((4r + 2kk + fk) & 15)) =
+    // ((frow ^ fk) ^ ((4r + 2kk) & 15)): a lane constant xor a uniform
+    const uint32_t b_off = (uint32_t)(fk * kStemBN) * 16u;
+    const uint32_t b_lane = (uint32_t)(frow ^ fk) * 16u;
+    const uint32_t row_bytes = (uint32_t)g.PPAIRS * 16u;
+    // which of the lane's two pixels per K slice are padding positions of the run; their weights
+    // are zero, but the input there is zeroed too so that a non-finite neighbour cannot leak in
     bool zero_lo[2], zero_hi[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
@@ -143,71 +193,163 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
         zero_lo[kk] = j < g.shift || j >= s.S + g.shift;
         zero_hi[kk] = (j + 1) < g.shift || (j + 1) >= s.S + g.shift;
     }
+    const bool mask_kk0 = g.shift != 0 || s.S + g.shift < 4;      // uniform: slice kk holds a padding slot
+    const bool mask_kk1 = s.S + g.shift < 8;
     const bool vec_ok = (s.K & 3) == 0;
 
+    // Output staging (vec_ok): each 32-pixel x 32-filter fragment goes through a 4 KiB area private
+    // to the wave, so that 8 lanes store one pixel's 128 contiguous bytes (a whole cache line)
+    // instead of 32 lanes storing 32 bytes of 32 different lines.  The 16-byte piece c of pixel t
+    // sits at piece c ^ ((t >> 1) & 7): both the deposit (16 lanes = 16 pixels, one piece) and the
+    // read-back (16 lanes = 2 pixels, 8 pieces) then cover all banks once.  LDS operations of one
+    // wave execute in order, so no wait is needed between deposit and read-back.
+    char* stg = reinterpret_cast<char*>(lds) + g.b_bytes + 2 * g.patch_bytes + wave * 4096;
+    const int c8 = lane & 7, l3 = lane >> 3;
+    uint32_t sw[4], sr[2];                        // deposit offset per filter quad; read-back offset, even/odd j
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) sw[gq] = (uint32_t)(frow * 8 + ((2 * gq + fk) ^ ((frow >> 1) & 7))) * 16u;
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) sr[jj] = (uint32_t)(l3 * 8 + (c8 ^ ((4 * jj + (lane >> 4)) & 7))) * 16u;
+    // the lane's piece of pixel 8j + l/8 of fragment mi lies at y_lane + (a uniform offset of (mi, j))
+    // bytes from the block's origin: 8j + l/8 < 32 <= 32 * (fragment index), and TW is 16 or 32
+    const uint32_t y_lane = (uint32_t)(l3 * s.K + 4 * c8) * (uint32_t)sizeof(TO);
+    bool k_ok[2];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) k_ok[ni] = k0 + ni * 32 + 4 * c8 + 3 < s.K;
+    const size_t y_elems = (size_t)s.M * s.K;
+
+    park_patch(0, pregs);
     __syncthreads();                            // weights and patch 0 are in LDS
     for (int tile = t_begin; tile < t_end; ++tile) {
-        const u32x4* patch = lds + ((g.b_bytes + ((tile - t_begin) & 1) * g.patch_bytes) >> 4);
+        if (tile + 1 < t_end) load_patch(tile + 1, pregs);
+        const char* pa = lds_b + g.b_bytes + ((tile - t_begin) & 1) * g.patch_bytes;
+        const char* pb = lds_b + b_off;
         floatx16 acc[MI][2];
+        frag_t a0[MI], b0[2], a1[MI], b1[2];    // operands of the two K slices of a filter row
+
+        auto fetch = [&](int r, int kk, frag_t (&af)[MI], frag_t (&bf)[2]) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
+                af[mi] = *reinterpret_cast<const frag_t*>(pa + a_off[mi] + (uint32_t)r * row_bytes + kk * 32);
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-        for (int r = 0; r < s.R; ++r) {
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                frag_t af[MI], bfr[2];
+                bf[ni] = *reinterpret_cast<const frag_t*>(pb + (b_lane ^ (uint32_t)(((4 * r + 2 * kk) & 15) << 4)) + r * 4096 +
+                                                          kk * 2048 + ni * 512);
+        };
+        auto mma = [&](frag_t (&af)[MI], frag_t (&bf)[2], int kk, bool first) {
+            if (kk == 0 ? mask_kk0 : mask_kk1) {
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi) {
-                    u32x4 v = patch[a_idx[mi] + r * g.PPAIRS + 2 * kk];
+                    u32x4 v = __builtin_bit_cast(u32x4, af[mi]);
                     if (zero_lo[kk]) { v.x = 0u; v.y = 0u; }
                     if (zero_hi[kk]) { v.z = 0u; v.w = 0u; }
                     af[mi] = __builtin_bit_cast(frag_t, v);
                 }
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    bfr[ni] = __builtin_bit_cast(frag_t, lds[(r * 4 + 2 * kk + fk) * kStemBN + ni * 32 + frow]);
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Elem<T>::mfma32(bfr[ni], af[mi], acc[mi][ni]);
             }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    if (first) {
+                        floatx16 z;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                        acc[mi][ni] = Elem<T>::mfma32(bf[ni], af[mi], z);
+                    } else {
+                        acc[mi][ni] = Elem<T>::mfma32(bf[ni], af[mi], acc[mi][ni]);
+                    }
+                }
+        };
+        // the operands of the next use of a slice are read from LDS while the other slice's MFMAs run
+        // (the fetch after the last row re-reads that row: unconditional, so that the number of LDS
+        // reads in flight is known at every wait)
+        const int r_last = s.R - 1;
+        fetch(0, 0, a0, b0);
+        fetch(0, 1, a1, b1);
+        mma(a0, b0, 0, true);
+        fetch(min(1, r_last), 0, a0, b0);
+        mma(a1, b1, 1, false);
+        for (int r = 1; r < s.R; ++r) {
+            fetch(r, 1, a1, b1);
+            mma(a0, b0, 0, false);
+            fetch(min(r + 1, r_last), 0, a0, b0);
+            mma(a1, b1, 1, false);
         }
 
         // ---- epilogue: lane l holds block pixel 32*frag + l%32 and, in accumulator element v, filter
         // 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block (the filters are the MFMA's row operand).
         const StemTile tc = stem_decode(tile, g);
+        if (vec_ok) {
+            // stores go through a buffer descriptor that starts at the block's first output
+            const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K + k0;
+            const size_t rem = (y_elems - org) * sizeof(TO);
+            const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0xffffffffull ? 0xffffffffu : (uint32_t)rem,
+                                                                   kRsrcFlags);
+            const bool edge = npx < BM || tc.p0 + g.TH > s.P || tc.q0 + TW > s.Q;    // uniform
+            // deposits and read-backs of all fragments are issued back to back through the same 4 KiB
+            // (in order within the wave), the stores follow as the read-backs arrive
+            u32x4 out[MI][2][4];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
-            if (p < s.P && q < s.Q) {
-                TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
+            for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        u32x4 v;
+                        v.x = __float_as_uint(acc[mi][ni][4 * gq]);     v.y = __float_as_uint(acc[mi][ni][4 * gq + 1]);
+                        v.z = __float_as_uint(acc[mi][ni][4 * gq + 2]); v.w = __float_as_uint(acc[mi][ni][4 * gq + 3]);
+                        *reinterpret_cast<u32x4*>(stg + sw[gq]) = v;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[mi][ni][j] = *reinterpret_cast<const u32x4*>(stg + sr[j & 1] + j * 1024);
+                }
+            }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni) {
 #pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        const int col = k0 + ni * 32 + 8 * gq + 4 * fk;
-                        if (vec_ok && col + 3 < s.K) {
-                            store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
-                                       acc[mi][ni][4 * gq + 3]);
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
+                    for (int j = 0; j < 4; ++j) {
+                        bool ok = k_ok[ni];
+                        if (edge) {
+                            const int t = (wave * MI + mi) * 32 + 8 * j + l3;
+                            ok = ok && t < npx && tc.p0 + (t >> g.TW_LOG2) < s.P && tc.q0 + (t & (TW - 1)) < s.Q;
                         }
+                        const int t0 = (wave * MI + mi) * 32 + 8 * j;       // uniform
+                        const uint32_t y_uni = (uint32_t)(((t0 >> g.TW_LOG2) * s.Q + (t0 & (TW - 1))) * s.K + ni * 32) * (uint32_t)sizeof(TO);
+                        if (ok) store_piece<TO>(out[mi][ni][j], y_rsrc, y_lane + y_uni);
                     }
                 }
             }
+        } else {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int t = (wave * MI + mi) * 32 + frow;
+                const int p = tc.p0 + (t >> g.TW_LOG2), q = tc.q0 + (t & (TW - 1));
+                if (t < npx && p < s.P && q < s.Q) {
+                    TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int col = k0 + ni * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+                            if (col < s.K) yrow[col] = to_out<TO>(acc[mi][ni][v]);
+                        }
+                }
+            }
         }
-        __syncthreads();                        // next patch has landed; this patch buffer may be refilled
+        // the other buffer was last read for the previous block, which every wave finished before
+        // the barrier that ended it
+        if (tile + 1 < t_end) park_patch((tile + 1 - t_begin) & 1, pregs);
+        __syncthreads();                        // next patch is in LDS; this block's buffer may be refilled
     }
 }
 
 constexpr int kStemMI = 2;                       // 4 waves x 2 fragments x 32 = 256 output pixels per block
-constexpr int kStemLdsLimit = 64 * 1024;
+constexpr int kStemLdsLimit = 80 * 1024;     // two workgroups per compute unit
+constexpr int kStemStageBytes = kStemWaves * 4096;
 
 bool plan_stem(const ConvShape& s, StemGeom* g) {
     if (s.C != 4 || s.dil != 1 || s.stride != 2 || (s.W & 1)) return false;
@@ -221,25 +363,34 @@ bool plan_stem(const ConvShape& s, StemGeom* g) {
     if (TH > s.P) TH = s.P;
     const int PH = (TH - 1) * s.stride + s.R;
     const int ppairs = ((TW - 1) * s.stride + 8) / 2;
-    const long patch_bytes = (((long)PH * ppairs + 63) / 64) * 1024;   // whole wave-wide loads
+    const long patch_bytes = (((long)PH * ppairs + 255) / 256) * 4096;   // whole workgroup-wide pieces
+    if (patch_bytes > kStemPatchItems * 4096) return false;
     const long b_bytes = (long)s.R * 4 * kStemBN * 16;
-    if (2 * patch_bytes + b_bytes > kStemLdsLimit) return false;
+    if (2 * patch_bytes + b_bytes + kStemStageBytes > kStemLdsLimit) return false;
+    if ((long)TH * s.Q * s.K * 4 >= (1L << 31)) return false;            // in-block output offsets are 32-bit
     g->TH = TH; g->TW_LOG2 = tw_log2; g->PH = PH; g->PPAIRS = ppairs;
     g->tiles_h = (s.P + TH - 1) / TH; g->tiles_w = (s.Q + TW - 1) / TW; g->tiles_n = (s.K + kStemBN - 1) / kStemBN;
     g->shift = shift; g->b_bytes = (int)b_bytes; g->patch_bytes = (int)patch_bytes; g->inv_ppairs = 1.0f / (float)ppairs;
     const long total = (long)s.N * g->tiles_h * g->tiles_w * g->tiles_n;
     if (total > 0x7fffffffL) return false;
     g->total_tiles = (int)total;
-    g->tiles_per_wg = 1;
     return true;
 }
 
 template <typename T, typename TO>
 hipError_t launch_stem_t(const void* x, const void* w, void* y, const ConvShape& s, StemGeom g, hipStream_t st) {
-    const int lds_bytes = g.b_bytes + 2 * g.patch_bytes;
+    const int lds_bytes = g.b_bytes + 2 * g.patch_bytes + kStemStageBytes;
     auto kern = stem_kernel<T, TO, kStemMI>;
-    const int threads = (kStemWaves + 1) * 64;
+    const int threads = kStemWaves * 64;
     int nwg = g.total_tiles;
+    // more than 64 KiB of dynamic LDS must be allowed once per kernel and process; a failed
+    // attempt is retried by the next call
+    static std::atomic<bool> raised{false};
+    if (!raised.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kStemLdsLimit);
+        if (e != hipSuccess) return e;
+        raised.store(true, std::memory_order_release);
+    }
     if (g.tiles_n == 1) {
         // one filter tile: workgroups own ranges of blocks and keep the weights resident
         static std::atomic<int> occ_lds{-1}, occ_val{1};
@@ -256,9 +407,11 @@ hipError_t launch_stem_t(const void* x, const void* w, void* y, const ConvShape&
         // filled (as many resident workgroups per compute unit as fit), each with an equal range.
         const int cap = g_max_workgroups.load(std::memory_order_relaxed);
         const long slots = cap > 0 ? cap : (long)device_cus() * occ;
-        g.tiles_per_wg = (int)((g.total_tiles + slots - 1) / slots);
-        nwg = (g.total_tiles + g.tiles_per_wg - 1) / g.tiles_per_wg;
+        const long per = (g.total_tiles + slots - 1) / slots;
+        nwg = (int)((g.total_tiles + per - 1) / per);
     }
+    g.tiles_base = g.total_tiles / nwg;
+    g.tiles_rem = g.total_tiles % nwg;
     hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(threads), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y, s, g);
     return hipGetLastError();
 }
