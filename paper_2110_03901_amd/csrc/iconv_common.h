@@ -81,6 +81,14 @@ bool patch_supported(const ConvShape& s, int v);
 hipError_t launch_patch(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
                         hipStream_t stream);
 
+// Resident-filter kernels (C % 32 == 0, K <= 64, K % 4 == 0, filters and input patch fit in LDS).
+int resident_num_variants();
+const char* resident_variant_name(int v);
+bool resident_supported(const ConvShape& s, int v);
+int resident_choose(const ConvShape& s);   // best variant or -1
+hipError_t launch_resident(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
+                           hipStream_t stream);
+
 // Merged-tap kernel for C == 4 first layers (stride 2, dilation 1, even W, S + (pad & 1) <= 8).
 bool stem_supported(const ConvShape& s);
 hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,

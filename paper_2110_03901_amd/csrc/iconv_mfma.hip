@@ -256,6 +256,9 @@ int choose_variant(const ConvShape& s) {
     const long tiles_256x128 = (long)((s.M + 255) / 256) * ((s.K + 127) / 128);
     const int P0 = kNumVariants;
     if (s.R * s.S > 1 && s.stride == 1) {
+        // few channels and filters: filters and patch resident in LDS
+        const int rv = resident_choose(s);
+        if (rv >= 0) return P0 + patch_num_variants() + rv;
         int v;
         if (s.K <= 64) v = P0 + 5;                    // p256x64, eight compute waves of 32x64
         else if (tiles_256x128 >= 200) v = P0 + 3;    // p256x128
@@ -276,16 +279,23 @@ int choose_variant(const ConvShape& s) {
 }  // namespace
 
 // Variant numbering seen through the C ABI: the per-tap kernels of this file first, then the
-// patch-reuse kernels.
-int mfma_num_variants() { return kNumVariants + patch_num_variants(); }
-const char* mfma_variant_name(int v) { return v < kNumVariants ? kVariantNames[v] : patch_variant_name(v - kNumVariants); }
+// patch-reuse kernels, then the resident-filter kernels.
+int mfma_num_variants() { return kNumVariants + patch_num_variants() + resident_num_variants(); }
+const char* mfma_variant_name(int v) {
+    if (v < kNumVariants) return kVariantNames[v];
+    if (v < kNumVariants + patch_num_variants()) return patch_variant_name(v - kNumVariants);
+    return resident_variant_name(v - kNumVariants - patch_num_variants());
+}
 
 hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int variant,
                        hipStream_t st) {
-    if (variant >= kNumVariants && patch_supported(s, variant - kNumVariants))
+    const int R0 = kNumVariants + patch_num_variants();        // first resident-filter variant
+    if (variant >= R0 && resident_supported(s, variant - R0)) return launch_resident(x, w, y, s, in_t, out_t, variant - R0, st);
+    if (variant >= kNumVariants && variant < R0 && patch_supported(s, variant - kNumVariants))
         return launch_patch(x, w, y, s, in_t, out_t, variant - kNumVariants, st);
     int v = variant;
-    if (v < 0 || v >= kNumVariants) v = choose_variant(s);    // also when a forced patch kernel does not fit
+    if (v < 0 || v >= kNumVariants) v = choose_variant(s);    // also when a forced kernel does not fit the layer
+    if (v >= R0) return launch_resident(x, w, y, s, in_t, out_t, v - R0, st);
     if (v >= kNumVariants) return launch_patch(x, w, y, s, in_t, out_t, v - kNumVariants, st);
     if (in_t == IN_BF16) {
         if (out_t == OUT_F32) return launch_variant<bf16_t, float>(v, x, w, y, s, st);

@@ -155,6 +155,33 @@ def test_workgroups_walking_several_tiles(B):
         B.iconv_set_max_workgroups(0)
 
 
+def test_resident_filter_kernels(B):
+    """The resident-filter kernels (filters of 64 output channels and the input patch of a block in
+    LDS): both fragment counts, forced, on shapes with one to four channel slices, strides,
+    dilation, ragged blocks and K < 64, uncapped and with workgroups walking through several
+    blocks (the next block's first slice is loaded while the last slice is computed)."""
+    shapes = [workloads.small_layer("r_a", 3, 20, 22, 64, 64, 3, 3, 1, 1, 1, seed_id=840),     # two slices
+              workloads.small_layer("r_b", 2, 17, 19, 32, 40, 3, 3, 1, 1, 1, seed_id=841),     # one slice, K = 40
+              workloads.small_layer("r_c", 2, 24, 24, 96, 64, 3, 3, 1, 2, 2, seed_id=842),     # three slices, dilated
+              workloads.small_layer("r_d", 1, 33, 31, 64, 48, 3, 3, 2, 1, 1, seed_id=843),     # stride 2
+              workloads.small_layer("r_e", 2, 30, 9, 128, 64, 1, 3, 1, 1, 1, dtype="f16", seed_id=844),   # 1x3, four slices
+              workloads.small_layer("r_f", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1, seed_id=845)]     # full-width blocks of 7 rows
+    names = [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
+    res = [v for v, nm in enumerate(names) if nm.startswith("r")]
+    assert len(res) == 2
+    try:
+        for cap in (0, 1, 3):
+            B.iconv_set_max_workgroups(cap)
+            for v in res:
+                B.iconv_set_variant(v)
+                for L in shapes:
+                    print("cap", cap, "variant", names[v], L.name, flush=True)
+                    check(B, L)
+    finally:
+        B.iconv_set_variant(-1)
+        B.iconv_set_max_workgroups(0)
+
+
 def test_merged_tap_workgroups_walking_several_blocks(B):
     """The merged-tap kernel for 4-channel layers keeps its weights in LDS and double-buffers the
     input patch over a range of output blocks: uncapped (few blocks per workgroup) and capped to
