@@ -10,18 +10,23 @@
 // (th*stride + r*dil, tw*stride + s*dil), a channel-contiguous run exactly as in section 3.1.
 // The filters stay for all blocks of a persistent workgroup.
 //
-// Waves.  Four compute waves (one per SIMD) each own MF*16 consecutive pixels of the block and
-// all 64 filters: MF x 4 accumulator tiles of the 16x16x32 MFMA, so one K step reads MF + 4
-// operand fragments for 4*MF MFMAs.  Output blocks of MF*64 pixels tile feature maps whose
-// width is a multiple of 7 or 8 without padding rows of the MFMA.  Two loader waves issue the
-// global -> LDS loads of the next channel slice (of this block or the next) while a slice is
-// computed; the loads of a workgroup's very first slice are shared by all six waves.
+// Waves.  Four compute waves (one per SIMD): wave w owns pixel half w/2 of the block (MF fragments
+// of 32 pixels) and filter half w%2 (32 filters), i.e. MF accumulator tiles of the 32x32x16 MFMA,
+// the instruction a single wave per SIMD can issue at full rate.  One K step of 16 channels reads
+// MF pixel fragments and one filter fragment for MF MFMAs.  Blocks of 64*MF pixels tile feature
+// maps whose width is a multiple of 7 (MF = 7) or 8 without padding rows of the MFMA.  Four loader
+// waves issue the global -> LDS loads: at the start those of the first NR phases (a phase is one
+// channel slice of one block; NR patch regions exist), the first phase's with the help of the
+// compute waves; afterwards, each time a phase has been computed, those of the phase that
+// reuses its region, so loading, computing and the previous block's stores overlap.
 //
 // LDS.  Patch slice and filter slice use the same layout: rows (a pixel, or a filter) of 64
-// bytes = four 16-byte chunks of 8 channels, chunk c of row i stored at chunk c ^ ((i >> 2) & 3).
+// bytes = four 16-byte chunks of 8 channels, chunk c of row i stored at chunk c ^ ((i >> 2) & 3);
+// patch rows are padded to a multiple of 16 pixels.
 // An operand read has 16 consecutive lanes on 16 consecutive rows and the same chunk, which
 // then fall on 16 different 16-byte positions of the 256-byte bank window.
 #include <atomic>
+#include <type_traits>
 
 #include "iconv_common.h"
 #include "iconv_device.h"
@@ -32,23 +37,23 @@ namespace iconv {
 namespace {
 
 constexpr int kResWaves = 4;         // compute waves
-constexpr int kResLoaders = 2;       // loader waves
+constexpr int kResLoaders = 4;       // loader waves
 constexpr int kResBN = 64;           // filters per workgroup
 constexpr int kResStage = 2048;      // output staging bytes per compute wave
 
 struct ResGeom {
     int TH, TW;          // output block
     int PH, PW;          // input patch
-    int npix;            // PH * PW
+    int PWp;             // PW rounded up to a multiple of 16: pixels per patch row in LDS
     int tiles_h, tiles_w;
     int total_tiles;
     int tiles_base, tiles_rem;   // workgroup i owns tiles_base (+1 if i < tiles_rem) consecutive blocks
     int KS;              // channel slices of 32
-    int NR;              // patch regions in LDS: max(KS, 2)
+    int NR;              // patch regions in LDS (2 .. 4); phase p uses region p % NR
     int slice_bytes;     // LDS bytes of one patch region (multiple of 1024)
     int w_bytes;         // LDS bytes of the filters: R*S*C*128
-    int patch_loads;     // wave-wide loads per patch slice
-    float inv_tw, inv_pw, inv_s;
+    int patch_loads;     // wave-wide loads per patch slice: PH * PWp / 16
+    float inv_tw;
 };
 
 struct ResTile {
@@ -64,24 +69,27 @@ __device__ __forceinline__ ResTile res_decode(int t, const ResGeom& g) {
     return c;
 }
 
-template <typename T> struct Mfma16;
-template <> struct Mfma16<bf16_t> {
-    static __device__ __forceinline__ floatx4 run(bf16x8 a, bf16x8 b, floatx4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n (n >= 63 waits for nothing more than vmcnt(63))
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+    switch (n) {
+#define ICONV_W(k) case k: wait_vmcnt<k>(); break;
+        ICONV_W(0) ICONV_W(1) ICONV_W(2) ICONV_W(3) ICONV_W(4) ICONV_W(5) ICONV_W(6) ICONV_W(7)
+        ICONV_W(8) ICONV_W(9) ICONV_W(10) ICONV_W(11) ICONV_W(12) ICONV_W(13) ICONV_W(14) ICONV_W(15)
+        ICONV_W(16) ICONV_W(17) ICONV_W(18) ICONV_W(19) ICONV_W(20) ICONV_W(21) ICONV_W(22) ICONV_W(23)
+        ICONV_W(24) ICONV_W(25) ICONV_W(26) ICONV_W(27) ICONV_W(28) ICONV_W(29) ICONV_W(30) ICONV_W(31)
+        ICONV_W(32) ICONV_W(33) ICONV_W(34) ICONV_W(35) ICONV_W(36) ICONV_W(37) ICONV_W(38) ICONV_W(39)
+        ICONV_W(40) ICONV_W(41) ICONV_W(42) ICONV_W(43) ICONV_W(44) ICONV_W(45) ICONV_W(46) ICONV_W(47)
+#undef ICONV_W
+        default: wait_vmcnt<0>(); break;
     }
-};
-template <> struct Mfma16<f16_t> {
-    static __device__ __forceinline__ floatx4 run(f16x8 a, f16x8 b, floatx4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-    }
-};
+}
 
-template <typename T, typename TO, int MF>
+template <typename T, typename TO, int MF, int S_>
 __global__ void __launch_bounds__((kResWaves + kResLoaders) * 64)
 ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const ResGeom g) {
     typedef typename Elem<T>::frag frag_t;
     constexpr int NWAVES = kResWaves + kResLoaders;
-    // [filters: (slice, tap, filter 0..63) x 64 B][NR patch regions: pixel x 64 B][staging: 2 KiB per compute wave]
+    // [filters: (slice, tap, filter 0..63) x 64 B][NR patch regions: padded patch pixel x 64 B][staging: 2 KiB per compute wave]
     extern __shared__ u32x4 lds[];
 
     const int tid = threadIdx.x;
@@ -91,168 +99,224 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     const int wg = xcd_remap(blockIdx.x, gridDim.x);
     const int t_begin = wg * g.tiles_base + min(wg, g.tiles_rem);
     const int t_end = t_begin + g.tiles_base + (wg < g.tiles_rem ? 1 : 0);
-    const int RS = s.R * s.S;
+    const int RS = s.R * S_;
     const int phases = (t_end - t_begin) * g.KS;             // (block, channel slice) pairs of this workgroup
     if (phases <= 0) return;
 
     // ---- global -> LDS loads of one phase, split over `nparts` waves (this wave is `part`).
-    // Wave-wide load j of a slice fills rows 16j .. 16j+15: lane l fetches row 16j + l/4, the
-    // logical chunk that lives at physical chunk l%4 of that row.
+    // A wave-wide load fills 16 rows of 64 bytes: lane l fetches row l/4 of the group and the
+    // logical chunk that lives at physical chunk l%4 of that row.  Patch rows are padded to a
+    // multiple of 16 pixels and the filters of a tap come in groups of 16, so the row number
+    // within the group alone decides the swizzle: the lane's chunk is the same for every load.
     const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * s.C * 2u;
     const uint32_t w_bytes = (uint32_t)s.K * s.Kg * 2u;
     const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
     const rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(w), 0, w_bytes, kRsrcFlags);
     const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)lds;
-    const int l_row = lane >> 2, l_pc = lane & 3;
+    const int l_row = lane >> 2;
+    const int l_chunk = (lane & 3) ^ ((l_row >> 2) & 3);
+    const uint32_t x_lane = (uint32_t)(l_row * s.C + l_chunk * 8) * 2u;       // byte offset of the lane within a 16-pixel group
+    const uint32_t w_lane = (uint32_t)(l_row * s.Kg + l_chunk * 8) * 2u;      // ... within a 16-filter group
+    const int groups = g.PWp >> 4;                                            // 16-pixel groups per patch row
+    // Returns the number of loads this wave issued (the same for every lane).
     auto issue_loads = [&](int phase, int part, int nparts) {
         const int ks = phase % g.KS;
-        int in_flight = 0;
+        int issued = 0;
         if (phase < g.KS) {
             // filters of this slice (first block only): load j covers tap j/4, filters 16*(j%4) + l/4
-            for (int j = part; j < RS * 4; j += nparts) {
-                const int f = (j & 3) * 16 + l_row;
-                const int chunk = l_pc ^ ((f >> 2) & 3);
-                const uint32_t off = (uint32_t)(f * s.Kg + (j >> 2) * s.C + ks * 32 + chunk * 8) * 2u;
-                dma16(w_rsrc, f < s.K ? off : w_bytes,
+            for (int j = part; j < RS * 4; j += nparts, ++issued) {
+                const int f0 = (j & 3) * 16;
+                const uint32_t off = (uint32_t)(f0 * s.Kg + (j >> 2) * s.C + ks * 32) * 2u + w_lane;
+                dma16(w_rsrc, f0 + l_row < s.K ? off : w_bytes,
                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + (uint32_t)((ks * RS * 4 + j) * 1024))));
-                if (++in_flight == 24) { wait_vmcnt<16>(); in_flight = 16; }
             }
         }
         const ResTile tc = res_decode(t_begin + phase / g.KS, g);
         const int h_org = tc.p0 * s.stride - s.pad, w_org = tc.q0 * s.stride - s.pad;
         const uint32_t region = lds_base + (uint32_t)g.w_bytes + (uint32_t)(phase % g.NR) * (uint32_t)g.slice_bytes;
-        for (int j = part; j < g.patch_loads; j += nparts) {
-            const int pp = j * 16 + l_row;
-            const int ph = (int)(((float)pp + 0.5f) * g.inv_pw);
-            const int pw = pp - ph * g.PW;
-            const int h = h_org + ph, ww = w_org + pw;
-            const bool ok = (pp < g.npix) & ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W);
-            const int chunk = l_pc ^ ((pp >> 2) & 3);
-            const uint32_t off = (uint32_t)(((tc.n * s.H + h) * s.W + ww) * s.C + ks * 32 + chunk * 8) * 2u;
-            dma16(x_rsrc, ok ? off : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)(region + (uint32_t)(j * 1024))));
-            if (++in_flight == 24) { wait_vmcnt<16>(); in_flight = 16; }
+        int row = part / groups, grp = part - row * groups;             // load j = row * groups + grp
+        const int drow = nparts / groups, dgrp = nparts - drow * groups;
+        for (int j = part; j < g.patch_loads; j += nparts, ++issued) {
+            const int h = h_org + row, w0 = w_org + grp * 16;
+            const bool row_ok = (unsigned)h < (unsigned)s.H;                // uniform
+            const uint32_t base = (uint32_t)(((tc.n * s.H + h) * s.W + w0) * s.C + ks * 32) * 2u;   // uniform; wraps when out of range
+            const bool ok = row_ok & ((unsigned)(w0 + l_row) < (unsigned)s.W);
+            dma16(x_rsrc, ok ? base + x_lane : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)(region + (uint32_t)(j * 1024))));
+            grp += dgrp; row += drow;
+            if (grp >= groups) { grp -= groups; ++row; }
         }
+        return issued;
     };
 
     issue_loads(0, wave, NWAVES);               // the first phase's loads are shared by all waves
 
     if (wave >= kResWaves) {
         // =========================== loader waves ===========================================
+        // Phase q may be loaded once phase q - NR (the previous user of its region) has been
+        // computed by every wave, i.e. after barrier q - NR + 1.  The host keeps a wave's loads of
+        // NR - 1 phases plus its share of the first phase below the 6-bit range of vmcnt.
         const int lw = wave - kResWaves;
+        // W: the phase the next wait is for.  later_i: loads this wave has issued for phase W + 1 + i
+        // (NR <= 4, so at most W + 2 is in flight at a wait); after = their sum.
+        int later0 = 0, later1 = 0, after = 0, issued_upto = 0;
         for (int p = 0; p < phases; ++p) {
-            wait_vmcnt<0>();
+            wait_vmcnt_dyn(after);              // W = p: everything up to phase p has landed
             __syncthreads();                    // phase p is in LDS; every wave has finished phase p - 1
-            // region (p + 1) % NR was last read in phase p + 1 - NR <= p - 1
-            if (p + 1 < phases) issue_loads(p + 1, lw, kResLoaders);
+            after -= later0;                    // W = p + 1
+            later0 = later1; later1 = 0;
+            while (issued_upto + 1 < phases && issued_upto + 1 <= p + g.NR - 1) {
+                const int q = ++issued_upto;
+                const int c = issue_loads(q, lw, kResLoaders);
+                const int i = q - (p + 2);      // q = (W + 1) + i; i < 0: q is the phase waited for next
+                if (i == 0) { later0 = c; after += c; }
+                if (i == 1) { later1 = c; after += c; }
+            }
         }
         return;
     }
 
     // =============================== compute waves ==============================================
-    const int l16 = lane & 15, lc = lane >> 4, lc16 = lc << 4;
+    const int frow = lane & 31, fk = lane >> 5;
+    const int m_half = wave >> 1, nh = wave & 1;
     const int npx = g.TH * g.TW;
     const char* lds_b = reinterpret_cast<const char*>(lds);
-    int a_pix[MF];                              // patch pixel of the lane's output pixel at tap (0, 0), per fragment
+    // Byte offset in a patch region of the lane's operand of fragment mf, tap column s, filter row 0
+    // and K step 0: pixel (th*stride, tw*stride + s*dil) of the padded patch, chunk l/32 (K step 1:
+    // chunk 2 + l/32, i.e. the offset xor 32).  A filter row further down adds a multiple of 1 KiB,
+    // which leaves the swizzle bits alone, so one add per operand read is all the arithmetic.
+    uint32_t a_addr[MF][S_];
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf) {
-        const int t = (wave * MF + mf) * 16 + l16;
+        const int t = (m_half * MF + mf) * 32 + frow;
         const int th = (int)(((float)t + 0.5f) * g.inv_tw);
         const int tw = t - th * g.TW;
-        a_pix[mf] = t < npx ? (th * g.PW + tw) * s.stride : 0;
+#pragma unroll
+        for (int sc = 0; sc < S_; ++sc) {
+            const int pix = t < npx ? (th * g.PWp + tw) * s.stride + sc * s.dil : sc * s.dil;
+            a_addr[mf][sc] = (uint32_t)(pix * 64 + ((fk ^ ((pix >> 2) & 3)) << 4));
+        }
     }
-    // filter fragment nf of (slice, tap): filter 16*nf + l%16, chunk l/16
-    const uint32_t b_lane = (uint32_t)(l16 * 64 + ((lc ^ (l16 >> 2)) << 4));
-    // output staging, 16 pixels x 32 filters at a time: piece c (16 bytes) of pixel i at i*128 + ((c ^ ((i >> 1) & 7)) << 4)
+    const uint32_t row_step = (uint32_t)(s.dil * g.PWp * 64);
+    // filter fragment of (slice, tap, K step kk): filter f = 32*nh + l%32, chunk 2*kk + l/32
+    const int f_lane = nh * 32 + frow;
+    const uint32_t b_lane0 = (uint32_t)(f_lane * 64 + ((fk ^ ((f_lane >> 2) & 3)) << 4));
+    const uint32_t b_lane1 = b_lane0 ^ 32u;
+    // output staging, 16 pixels x 32 filters at a time: piece c (16 bytes, 4 filters) of pixel i at
+    // i*128 + ((c ^ ((i >> 1) & 7)) << 4)
     char* stg = reinterpret_cast<char*>(lds) + g.w_bytes + g.NR * g.slice_bytes + wave * kResStage;
-    const uint32_t sw0 = (uint32_t)(l16 * 128 + ((lc ^ ((l16 >> 1) & 7)) << 4));        // pieces lc (first filter block), lc + 4
-    const uint32_t sw1 = (uint32_t)(l16 * 128 + (((lc + 4) ^ ((l16 >> 1) & 7)) << 4));
+    const int f16 = frow & 15;
+    const uint32_t sw0 = (uint32_t)(f16 * 128 + ((fk ^ ((f16 >> 1) & 7)) << 4));        // piece 2*gq + fk: xor (gq << 5)
     const int l8 = lane >> 3, c8 = lane & 7;
     const uint32_t sr0 = (uint32_t)(l8 * 128 + ((c8 ^ ((l8 >> 1) & 7)) << 4));          // pixel l/8 (+8), piece l%8
     const uint32_t sr1 = (uint32_t)((l8 + 8) * 128 + ((c8 ^ (((l8 + 8) >> 1) & 7)) << 4));
     const size_t y_elems = (size_t)s.M * s.K;
+    const bool k_ok = nh * 32 + 4 * c8 + 3 < s.K;
 
     wait_vmcnt<0>();                            // this wave's share of the first phase's loads
-    floatx4 acc[MF][4];
+    floatx16 acc[MF];
     for (int p = 0; p < phases; ++p) {
         __syncthreads();                        // phase p is in LDS
         const int ks = p % g.KS;
-        const char* pa = lds_b + g.w_bytes + (p % g.NR) * g.slice_bytes;
-        const char* pb = lds_b + b_lane + ks * RS * 4096;
-        frag_t af[MF], b0[4], b1[4];
+        const uint32_t pa = lds_base + (uint32_t)(g.w_bytes + (p % g.NR) * g.slice_bytes);   // LDS address of the patch region
+        const char* pb = lds_b + ks * RS * 4096;
+        frag_t af[MF], b0, b1;
 
-        auto tap_offset = [&](int t) {
-            const int r = (int)(((float)t + 0.5f) * g.inv_s);
-            return (r * g.PW + (t - r * s.S)) * s.dil;
+        // K steps of a filter row r: (s, kk) = (0,0), (0,1), (1,0), ... (S-1, 1); kk selects 16 of the
+        // slice's 32 channels.  In every step the filter fragment of the next step is read into the
+        // other B register set first, and each pixel fragment is re-read for the next step as soon
+        // as its MFMA has been issued, so the LDS reads of a step run under the MFMAs of the step
+        // before.  (After the last row the reads repeat it: unconditional, and harmless.)  The
+        // scheduling barriers keep that order.
+        // (one instruction, (a ^ b) + c, written out so that the optimiser neither splits it nor keeps
+        // the xor-ed variants of all addresses in registers across the loop)
+        auto fetch_a = [&](int mf, int sc, int kk, uint32_t roff) {
+            uint32_t addr;
+            if (kk) asm volatile("v_xad_u32 %0, %1, 32, %2" : "=v"(addr) : "v"(a_addr[mf][sc]), "s"(roff));
+            else asm volatile("v_add_u32 %0, %1, %2" : "=v"(addr) : "s"(roff), "v"(a_addr[mf][sc]));
+            return *reinterpret_cast<const frag_t __attribute__((address_space(3)))*>(addr);
         };
-        auto fetch_a = [&](int tap_off, int mf) {
-            const int pix = a_pix[mf] + tap_off;
-            return *reinterpret_cast<const frag_t*>(pa + pix * 64 + (((pix << 2) & 0x30) ^ lc16));
+        auto fetch_b = [&](int tap, int kk) {
+            return *reinterpret_cast<const frag_t*>(pb + tap * 4096 + (kk ? b_lane1 : b_lane0));
         };
-        // One tap: the filter fragments of the next tap are read into the other B set first, and each
-        // pixel fragment is re-read for the next tap as soon as its four MFMAs have been issued, so
-        // the LDS reads of tap t + 1 run under the MFMAs of tap t with one A set and two B sets.
-        // (Past the last tap the reads repeat it: unconditional, and harmless.)
-        auto step = [&](int t_next, const frag_t (&bc)[4], frag_t (&bn)[4], bool first) {
-            const int off_next = tap_offset(t_next);
+        auto row = [&](int r, auto first) {
+            const int r_next = min(r + 1, s.R - 1);
+            const uint32_t roff = pa + (uint32_t)r * row_step, roff_next = pa + (uint32_t)r_next * row_step;
 #pragma unroll
-            for (int nf = 0; nf < 4; ++nf) bn[nf] = *reinterpret_cast<const frag_t*>(pb + t_next * 4096 + nf * 1024);
+            for (int st = 0; st < 2 * S_; ++st) {
+                const int sc = st >> 1, kk = st & 1;
+                const bool wrap = st + 1 == 2 * S_;                   // next step: first of the next row
+                const int sc_n = wrap ? 0 : (st + 1) >> 1, kk_n = wrap ? 0 : (st + 1) & 1;
+                frag_t& bc = (st & 1) ? b1 : b0;
+                frag_t& bn = (st & 1) ? b0 : b1;
+                bn = fetch_b((wrap ? r_next : r) * S_ + sc_n, kk_n);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                if (first) {
-                    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+                for (int mf = 0; mf < MF; ++mf) {
+                    if (decltype(first)::value && st == 0) {
+                        floatx16 z;
 #pragma unroll
-                    for (int nf = 0; nf < 4; ++nf) acc[mf][nf] = Mfma16<T>::run(bc[nf], af[mf], z);
-                } else {
-#pragma unroll
-                    for (int nf = 0; nf < 4; ++nf) acc[mf][nf] = Mfma16<T>::run(bc[nf], af[mf], acc[mf][nf]);
+                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                        acc[mf] = Elem<T>::mfma32(bc, af[mf], z);
+                    } else {
+                        acc[mf] = Elem<T>::mfma32(bc, af[mf], acc[mf]);
+                    }
+                    af[mf] = fetch_a(mf, sc_n, kk_n, wrap ? roff_next : roff);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                af[mf] = fetch_a(off_next, mf);
+                (void)sc; (void)kk;
             }
         };
-        const int t_last = RS - 1;
+        b0 = fetch_b(0, 0);
 #pragma unroll
-        for (int nf = 0; nf < 4; ++nf) b0[nf] = *reinterpret_cast<const frag_t*>(pb + nf * 1024);
-#pragma unroll
-        for (int mf = 0; mf < MF; ++mf) af[mf] = fetch_a(0, mf);
-        for (int t = 0; t < RS; t += 2) {
-            step(min(t + 1, t_last), b0, b1, ks == 0 && t == 0);
-            if (t + 1 < RS) step(min(t + 2, t_last), b1, b0, false);
-        }
+        for (int mf = 0; mf < MF; ++mf) af[mf] = fetch_a(mf, 0, 0, pa);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks == 0) row(0, std::true_type{});  // a block's first step starts the accumulators
+        else row(0, std::false_type{});
+        for (int r = 1; r < s.R; ++r) row(r, std::false_type{});
         if (ks + 1 < g.KS) continue;
 
         // ---- epilogue of the block.  The filters are the MFMA's row operand: lane l holds pixel
-        // l%16 of fragment mf and filters 16*nf + 4*(l/16) .. +3 in acc[mf][nf].  Two filter blocks
-        // at a time go through the wave's staging area (in-order LDS, no wait needed in between)
-        // and leave as 16-byte pieces, 8 lanes per pixel = one 128-byte line of the y row.
+        // l%32 of fragment mf and, in accumulator element v, filter 32*nh + 8*(v/4) + 4*(l/32) + v%4.
+        // Half a fragment (16 pixels x 32 filters) at a time goes through the wave's staging area
+        // (in-order LDS, no wait needed in between) and leaves as 16-byte pieces, 8 lanes per pixel =
+        // one 128-byte line of the y row.
         const ResTile tc = res_decode(t_begin + p / g.KS, g);
         const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
         const size_t rem = (y_elems - org) * sizeof(TO);
         const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0xffffffffull ? 0xffffffffu : (uint32_t)rem,
                                                                kRsrcFlags);
+        // (opaque to the optimiser: the pixel arithmetic below is then redone per block instead of
+        // being kept in registers across the K loop, which has none to spare)
+        int l8v = l8;
+        asm volatile("" : "+v"(l8v));
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf) {
             u32x4 out[2][2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 __builtin_amdgcn_wave_barrier();
-                *reinterpret_cast<floatx4*>(stg + sw0) = acc[mf][2 * h];
-                *reinterpret_cast<floatx4*>(stg + sw1) = acc[mf][2 * h + 1];
+                if ((frow >> 4) == h) {
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        floatx4 v = {acc[mf][4 * gq], acc[mf][4 * gq + 1], acc[mf][4 * gq + 2], acc[mf][4 * gq + 3]};
+                        *reinterpret_cast<floatx4*>(stg + (sw0 ^ (uint32_t)(gq << 5))) = v;
+                    }
+                }
                 __builtin_amdgcn_wave_barrier();
                 out[h][0] = *reinterpret_cast<const u32x4*>(stg + sr0);
                 out[h][1] = *reinterpret_cast<const u32x4*>(stg + sr1);
             }
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int t = (wave * MF + mf) * 16 + 8 * j + l8;
-                const int th = (int)(((float)t + 0.5f) * g.inv_tw);
-                const int tw = t - th * g.TW;
-                const bool pix_ok = (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q);
-                const uint32_t off = (uint32_t)((th * s.Q + tw) * s.K + 4 * c8) * (uint32_t)sizeof(TO);
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    if (pix_ok && h * 32 + 4 * c8 + 3 < s.K)
-                        store_piece<TO>(out[h][j], y_rsrc, off + (uint32_t)(h * 32 * sizeof(TO)));
-            }
+                for (int j = 0; j < 2; ++j) {
+                    const int t = (m_half * MF + mf) * 32 + h * 16 + 8 * j + l8v;
+                    const int th = (int)(((float)t + 0.5f) * g.inv_tw);
+                    const int tw = t - th * g.TW;
+                    const bool ok = k_ok & (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q);
+                    const uint32_t off = (uint32_t)((th * s.Q + tw) * s.K + nh * 32 + 4 * c8) * (uint32_t)sizeof(TO);
+                    if (ok) store_piece<TO>(out[h][j], y_rsrc, off);
+                }
         }
     }
 }
@@ -263,10 +327,11 @@ constexpr int kResLdsLimit = 160 * 1024;
 // the patch-reuse kernels: MFMA work of all (padded) blocks plus the patch pixels brought into LDS.
 bool plan_res(const ConvShape& s, int MF, ResGeom* g, double* cost_out) {
     if ((s.C % 32) != 0 || (s.K & 3) != 0 || s.K > kResBN) return false;
-    const int BM = kResWaves * MF * 16;
+    if (s.S != 1 && s.S != 3) return false;                    // the filter width is a compile-time parameter
+    const int BM = 2 * MF * 32;          // two pixel halves of MF fragments; the wave pairs split the filters
     const int RS = s.R * s.S;
     const long w_lds = (long)s.Kg * 128;
-    const int KS = s.C / 32, NR = KS > 2 ? KS : 2;
+    const int KS = s.C / 32;
     double best = 1e300;
     bool found = false;
     for (int tw = 1; tw <= s.Q && tw <= BM; ++tw) {
@@ -275,22 +340,29 @@ bool plan_res(const ConvShape& s, int MF, ResGeom* g, double* cost_out) {
         if (th < 1) continue;
         const int ph = (th - 1) * s.stride + (s.R - 1) * s.dil + 1;
         const int pw = (tw - 1) * s.stride + (s.S - 1) * s.dil + 1;
-        const long npix = (long)ph * pw;
-        const long patch_loads = (npix + 15) / 16;
+        const int pwp = (pw + 15) & ~15;
+        const long patch_loads = (long)ph * (pwp / 16);
         const long slice_bytes = patch_loads * 1024;
+        // patch regions: one per channel slice when that fits (at most three), else two
+        int NR = KS < 2 ? 2 : (KS > 3 ? 3 : KS);
+        while (NR > 2 && w_lds + NR * slice_bytes + kResWaves * kResStage > kResLdsLimit) --NR;
         if (w_lds + NR * slice_bytes + kResWaves * kResStage > kResLdsLimit) continue;
-        if (npix >= (1 << 20)) continue;                                  // fp32 reciprocal index arithmetic
+        if ((long)ph * pwp >= (1 << 20)) continue;
+        // a loader wave's loads of NR - 1 phases (patch and, in the first block, filters) and its
+        // share of the first phase must stay countable by vmcnt
+        const long per_phase = (patch_loads + kResLoaders - 1) / kResLoaders + (RS * 4 + kResLoaders - 1) / kResLoaders;
+        if ((NR - 1) * per_phase + per_phase / 2 + 2 > 47) continue;
         if ((long)th * s.Q * s.K * 4 >= (1L << 31)) continue;             // in-block output offsets are 32-bit
         const long tiles = (long)((s.P + th - 1) / th) * ((s.Q + tw - 1) / tw);
-        const double cost = (double)tiles * ((double)BM * RS + 4.0 * (double)npix);
+        const double cost = (double)tiles * ((double)BM * RS + 4.0 * (double)ph * pwp);
         if (cost < best) {
             best = cost;
             found = true;
-            g->TH = th; g->TW = tw; g->PH = ph; g->PW = pw; g->npix = (int)npix;
+            g->TH = th; g->TW = tw; g->PH = ph; g->PW = pw; g->PWp = pwp;
             g->tiles_h = (s.P + th - 1) / th; g->tiles_w = (s.Q + tw - 1) / tw;
             g->KS = KS; g->NR = NR; g->slice_bytes = (int)slice_bytes; g->w_bytes = (int)w_lds;
             g->patch_loads = (int)patch_loads;
-            g->inv_tw = 1.0f / (float)tw; g->inv_pw = 1.0f / (float)pw; g->inv_s = 1.0f / (float)s.S;
+            g->inv_tw = 1.0f / (float)tw;
         }
     }
     if (!found) return false;
@@ -301,10 +373,10 @@ bool plan_res(const ConvShape& s, int MF, ResGeom* g, double* cost_out) {
     return true;
 }
 
-template <typename T, typename TO, int MF>
+template <typename T, typename TO, int MF, int S_>
 hipError_t launch_res_t(const void* x, const void* w, void* y, const ConvShape& s, ResGeom g, hipStream_t st) {
     const int lds_bytes = g.w_bytes + g.NR * g.slice_bytes + kResWaves * kResStage;
-    auto kern = ires_kernel<T, TO, MF>;
+    auto kern = ires_kernel<T, TO, MF, S_>;
     const int threads = (kResWaves + kResLoaders) * 64;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
@@ -332,19 +404,26 @@ hipError_t launch_res_t(const void* x, const void* w, void* y, const ConvShape& 
     return hipGetLastError();
 }
 
+template <int MF, int S_>
+hipError_t launch_res_ms(const void* x, const void* w, void* y, const ConvShape& s, const ResGeom& g, int in_t, int out_t,
+                         hipStream_t st) {
+    if (in_t == IN_BF16) {
+        if (out_t == OUT_F32) return launch_res_t<bf16_t, float, MF, S_>(x, w, y, s, g, st);
+        return launch_res_t<bf16_t, bf16_t, MF, S_>(x, w, y, s, g, st);
+    }
+    if (out_t == OUT_F32) return launch_res_t<f16_t, float, MF, S_>(x, w, y, s, g, st);
+    return launch_res_t<f16_t, f16_t, MF, S_>(x, w, y, s, g, st);
+}
+
 template <int MF>
 hipError_t launch_res_mf(const void* x, const void* w, void* y, const ConvShape& s, const ResGeom& g, int in_t, int out_t,
                          hipStream_t st) {
-    if (in_t == IN_BF16) {
-        if (out_t == OUT_F32) return launch_res_t<bf16_t, float, MF>(x, w, y, s, g, st);
-        return launch_res_t<bf16_t, bf16_t, MF>(x, w, y, s, g, st);
-    }
-    if (out_t == OUT_F32) return launch_res_t<f16_t, float, MF>(x, w, y, s, g, st);
-    return launch_res_t<f16_t, f16_t, MF>(x, w, y, s, g, st);
+    if (s.S == 1) return launch_res_ms<MF, 1>(x, w, y, s, g, in_t, out_t, st);
+    return launch_res_ms<MF, 3>(x, w, y, s, g, in_t, out_t, st);
 }
 
 constexpr int kResMF[] = {7, 8};
-const char* const kResNames[] = {"r448x64_f7_4+2", "r512x64_f8_4+2"};
+const char* const kResNames[] = {"r448x64_f7_4+4", "r512x64_f8_4+4"};
 
 }  // namespace
 
