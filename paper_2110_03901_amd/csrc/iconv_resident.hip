@@ -214,19 +214,20 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
 
     wait_vmcnt<0>();                            // this wave's share of the first phase's loads
     floatx16 acc[MF];
-    for (int p = 0; p < phases; ++p) {
-        __syncthreads();                        // phase p is in LDS
+
+    // ---- the K loop of phase p (one channel slice of a block) for fragments MF0 .. MF1-1.
+    // K steps of a filter row r: (s, kk) = (0,0), (0,1), (1,0), ... (S-1, 1); kk selects 16 of the
+    // slice's 32 channels.  In every step the filter fragment of the next step is read into the
+    // other B register set first, and each pixel fragment is re-read for the next step as soon as
+    // its MFMA has been issued, so the LDS reads of a step run under the MFMAs of the step before.
+    // (After the last row the reads repeat it: unconditional, and harmless.)  The scheduling
+    // barriers keep that order.
+    auto compute_slice = [&](int p, auto mf0_t, auto mf1_t) {
+        constexpr int MF0 = decltype(mf0_t)::value, MF1 = decltype(mf1_t)::value;
         const int ks = p % g.KS;
         const uint32_t pa = lds_base + (uint32_t)(g.w_bytes + (p % g.NR) * g.slice_bytes);   // LDS address of the patch region
         const char* pb = lds_b + ks * RS * 4096;
         frag_t af[MF], b0, b1;
-
-        // K steps of a filter row r: (s, kk) = (0,0), (0,1), (1,0), ... (S-1, 1); kk selects 16 of the
-        // slice's 32 channels.  In every step the filter fragment of the next step is read into the
-        // other B register set first, and each pixel fragment is re-read for the next step as soon
-        // as its MFMA has been issued, so the LDS reads of a step run under the MFMAs of the step
-        // before.  (After the last row the reads repeat it: unconditional, and harmless.)  The
-        // scheduling barriers keep that order.
         // (one instruction, (a ^ b) + c, written out so that the optimiser neither splits it nor keeps
         // the xor-ed variants of all addresses in registers across the loop)
         auto fetch_a = [&](int mf, int sc, int kk, uint32_t roff) {
@@ -243,7 +244,6 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
             const uint32_t roff = pa + (uint32_t)r * row_step, roff_next = pa + (uint32_t)r_next * row_step;
 #pragma unroll
             for (int st = 0; st < 2 * S_; ++st) {
-                const int sc = st >> 1, kk = st & 1;
                 const bool wrap = st + 1 == 2 * S_;                   // next step: first of the next row
                 const int sc_n = wrap ? 0 : (st + 1) >> 1, kk_n = wrap ? 0 : (st + 1) & 1;
                 frag_t& bc = (st & 1) ? b1 : b0;
@@ -251,7 +251,7 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
                 bn = fetch_b((wrap ? r_next : r) * S_ + sc_n, kk_n);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int mf = 0; mf < MF; ++mf) {
+                for (int mf = MF0; mf < MF1; ++mf) {
                     if (decltype(first)::value && st == 0) {
                         floatx16 z;
 #pragma unroll
@@ -263,24 +263,25 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
                     af[mf] = fetch_a(mf, sc_n, kk_n, wrap ? roff_next : roff);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                (void)sc; (void)kk;
             }
         };
         b0 = fetch_b(0, 0);
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf) af[mf] = fetch_a(mf, 0, 0, pa);
+        for (int mf = MF0; mf < MF1; ++mf) af[mf] = fetch_a(mf, 0, 0, pa);
         __builtin_amdgcn_sched_barrier(0);
         if (ks == 0) row(0, std::true_type{});  // a block's first step starts the accumulators
         else row(0, std::false_type{});
         for (int r = 1; r < s.R; ++r) row(r, std::false_type{});
-        if (ks + 1 < g.KS) continue;
+    };
 
-        // ---- epilogue of the block.  The filters are the MFMA's row operand: lane l holds pixel
-        // l%32 of fragment mf and, in accumulator element v, filter 32*nh + 8*(v/4) + 4*(l/32) + v%4.
-        // Half a fragment (16 pixels x 32 filters) at a time goes through the wave's staging area
-        // (in-order LDS, no wait needed in between) and leaves as 16-byte pieces, 8 lanes per pixel =
-        // one 128-byte line of the y row.
-        const ResTile tc = res_decode(t_begin + p / g.KS, g);
+    // ---- the epilogue of a block for fragments MF0 .. MF1-1.  The filters are the MFMA's row
+    // operand: lane l holds pixel l%32 of fragment mf and, in accumulator element v, filter
+    // 32*nh + 8*(v/4) + 4*(l/32) + v%4.  Half a fragment (16 pixels x 32 filters) at a time goes
+    // through the wave's staging area (in-order LDS, no wait needed in between) and leaves as
+    // 16-byte pieces, 8 lanes per pixel = one 128-byte line of the y row.
+    auto epilogue = [&](int tile, auto mf0_t, auto mf1_t) {
+        constexpr int MF0 = decltype(mf0_t)::value, MF1 = decltype(mf1_t)::value;
+        const ResTile tc = res_decode(tile, g);
         const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
         const size_t rem = (y_elems - org) * sizeof(TO);
         const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0xffffffffull ? 0xffffffffu : (uint32_t)rem,
@@ -290,7 +291,7 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
         int l8v = l8;
         asm volatile("" : "+v"(l8v));
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf) {
+        for (int mf = MF0; mf < MF1; ++mf) {
             u32x4 out[2][2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -318,6 +319,17 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
                     if (ok) store_piece<TO>(out[h][j], y_rsrc, off);
                 }
         }
+    };
+
+    // (Computing and storing a single block in two groups of fragments, so that the first group's
+    // stores drain under the second group's MFMAs, was measured and is slower: a wave's stores
+    // block it for as long as the memory system takes to accept them.)
+    constexpr std::integral_constant<int, 0> kZero{};
+    constexpr std::integral_constant<int, MF> kAll{};
+    for (int p = 0; p < phases; ++p) {
+        __syncthreads();                        // phase p is in LDS
+        compute_slice(p, kZero, kAll);
+        if (p % g.KS + 1 == g.KS) epilogue(t_begin + p / g.KS, kZero, kAll);
     }
 }
 
@@ -328,6 +340,7 @@ constexpr int kResLdsLimit = 160 * 1024;
 bool plan_res(const ConvShape& s, int MF, ResGeom* g, double* cost_out) {
     if ((s.C % 32) != 0 || (s.K & 3) != 0 || s.K > kResBN) return false;
     if (s.S != 1 && s.S != 3) return false;                    // the filter width is a compile-time parameter
+    if (MF == 8 && s.S == 3) return false;                     // eight fragments and three address sets exceed the register file
     const int BM = 2 * MF * 32;          // two pixel halves of MF fragments; the wave pairs split the filters
     const int RS = s.R * s.S;
     const long w_lds = (long)s.Kg * 128;
