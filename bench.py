@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0       # HBM3E, MI355X datasheet
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, scaled by the same counters' reading for the copy probe (see profiles/): layer -> bytes
-MEASURED_TRAFFIC_BYTES = {"cfg2": 39_250_000, "cfg3a": 41_080_000, "cfg3b": 67_470_000, "cfg4": 59_940_000,
-                          "cfg5a": 233_240_000, "cfg5b": 47_500_000}   # profiles/bench_all_layers_pmc.txt
+MEASURED_TRAFFIC_BYTES = {"cfg2": 39_350_000, "cfg3a": 41_080_000, "cfg3b": 67_470_000, "cfg4": 59_940_000,
+                          "cfg5a": 242_590_000, "cfg5b": 47_500_000}   # profiles/bench_all_layers_pmc.txt
 
 
 def main():
@@ -188,7 +188,7 @@ def main():
             conv_ref(x, w, L.stride, L.pad, L.dilation)
             reps += 1
             el = time.perf_counter() - t0
-            if el > 10.0 or reps >= 12:
+            if el > 10.0 or reps >= 400:
                 break
         cpu_tflops = L.flops * reps / el / 1e12
         out["cpu_baseline"] = {"value": round(cpu_tflops, 5), "unit": "TFLOP/s", "cores": threads(), "kind": "oracle",

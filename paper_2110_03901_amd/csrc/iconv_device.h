@@ -28,6 +28,17 @@ __device__ __forceinline__ void dma16(rsrc_t rsrc, uint32_t voff, uint32_t lds_a
                  : "memory", "m0");
 }
 
+// The same with a wave-uniform byte offset `soff` added to the address through the instruction's
+// scalar offset operand, so that a lane-constant `voff` needs no vector arithmetic per load.
+// Callers keep voff + soff below 2^32 and pass in-range sums for every lane that is not meant to
+// read zeros; a lane meant to read zeros carries voff >= the buffer size.
+__device__ __forceinline__ void dma16s(rsrc_t rsrc, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
+}
+
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");

@@ -125,6 +125,9 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 
     if (wave >= WAVES_C && wave < WAVES_C + NLD) {
         // =========================== loader waves ===========================================
+        // Their instructions are few but on the critical path of every step: they take priority over
+        // the compute waves (which spend their time in MFMAs) at the instruction arbiter.
+        __builtin_amdgcn_s_setprio(3);
         const int lw = wave - WAVES_C;
         const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * s.C * 2u;
         const uint32_t w_bytes = (uint32_t)s.K * s.Kg * 2u;
@@ -179,31 +182,42 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         // ---- filter-tile loads (one BN x CB tile per step)
         const int pc = lane % CPR, lr = lane / CPR;
         const bool ragged_c = (s.C % CB) != 0;
+        // Offset of the lane's 16 bytes at tap (0, 0), chunk 0; filters past K carry w_bytes instead,
+        // which stays out of range (a zero load) whatever tap offset is added: the host checks that
+        // 2 * w_bytes fits 32 bits.
         uint32_t b_off[B_IT];
-        bool b_ok[B_IT];
         int b_tile = t_begin;                   // tile whose filters the next load belongs to
         auto filter_tile = [&]() {
             const TileCoord tc = decode_tile<BN>(b_tile, g);
 #pragma unroll
             for (int j = 0; j < B_IT; ++j) {
                 const int row = (lw + j * NLD) * RPB + lr;
-                b_ok[j] = (tc.k0 + row) < s.K;
-                b_off[j] = (uint32_t)((tc.k0 + row) * s.Kg + swz<CPR>(row, pc) * 8) * 2u;
+                b_off[j] = (tc.k0 + row) < s.K ? (uint32_t)((tc.k0 + row) * s.Kg + swz<CPR>(row, pc) * 8) * 2u : w_bytes;
             }
         };
         filter_tile();
         int lr_ = 0, ls_ = 0, lc0 = 0;          // tap (lr_, ls_) of channel chunk lc0 to load next
         auto filter_load = [&](int stage, bool live) {
-            const uint32_t delta = (uint32_t)((lr_ * s.S + ls_) * s.C + lc0) * 2u;
+            const uint32_t delta = (uint32_t)((lr_ * s.S + ls_) * s.C + lc0) * 2u;     // tap and chunk: uniform
+            if (!live) {
+                // a step past the end loads nothing (zeros), but keeps the count of loads in flight
 #pragma unroll
-            for (int j = 0; j < B_IT; ++j) {
-                bool ok = live & b_ok[j];
-                if (ragged_c) {
+                for (int j = 0; j < B_IT; ++j)
+                    dma16(w_rsrc, w_bytes, bstage_base + (uint32_t)(stage * BSTAGE_BYTES + (lw + j * NLD) * 1024));
+            } else if (ragged_c) {
+#pragma unroll
+                for (int j = 0; j < B_IT; ++j) {
                     const int row = (lw + j * NLD) * RPB + lr;
-                    ok = ok & ((lc0 + swz<CPR>(row, pc) * 8) < s.C);
+                    const bool ok = (lc0 + swz<CPR>(row, pc) * 8) < s.C;
+                    dma16(w_rsrc, ok ? b_off[j] + delta : w_bytes,
+                          bstage_base + (uint32_t)(stage * BSTAGE_BYTES + (lw + j * NLD) * 1024));
                 }
-                dma16(w_rsrc, ok ? b_off[j] + delta : w_bytes,
-                      bstage_base + (uint32_t)(stage * BSTAGE_BYTES + (lw + j * NLD) * 1024));
+            } else {
+                // the common case costs no vector instruction but the load itself
+#pragma unroll
+                for (int j = 0; j < B_IT; ++j)
+                    dma16s(w_rsrc, b_off[j], (uint32_t)__builtin_amdgcn_readfirstlane((int)delta),
+                           bstage_base + (uint32_t)(stage * BSTAGE_BYTES + (lw + j * NLD) * 1024));
             }
             if (++ls_ == s.S) {
                 ls_ = 0;
@@ -445,6 +459,7 @@ constexpr int kLdsLimit = 160 * 1024;
 // work of all (padded) tiles plus the patch pixels that have to be brought into LDS.
 bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
     const int BM = c.bm();
+    if ((double)s.K * s.Kg * 4.0 >= 4294967296.0) return false;   // out-of-range filter offsets must not wrap (see filter_tile)
     if (c.ss > 0) {
         // the staged epilogue stores through a 32-bit buffer descriptor, needs K % 4 == 0 for whole
         // 16-byte pieces, and must get a tile out within the steps of the next one

@@ -155,6 +155,7 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
         // Phase q may be loaded once phase q - NR (the previous user of its region) has been
         // computed by every wave, i.e. after barrier q - NR + 1.  The host keeps a wave's loads of
         // NR - 1 phases plus its share of the first phase below the 6-bit range of vmcnt.
+        __builtin_amdgcn_s_setprio(3);          // few instructions, on the critical path: ahead of the compute waves at the arbiter
         const int lw = wave - kResWaves;
         // W: the phase the next wait is for.  later_i: loads this wave has issued for phase W + 1 + i
         // (NR <= 4, so at most W + 2 is in flight at a wait); after = their sum.

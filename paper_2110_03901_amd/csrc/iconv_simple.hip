@@ -32,6 +32,9 @@ __global__ void __launch_bounds__(256) direct_kernel(const TI* __restrict__ x, c
                 if ((unsigned)ww >= (unsigned)s.W) continue;
                 const TI* xp = x + ((size_t)((size_t)n * s.H + h) * s.W + ww) * s.C;
                 const TI* wp = w + ((size_t)((size_t)k * s.R + r) * s.S + ss) * s.C;
+                // (unrolled so that the loads of several channels are in flight at once; the sum
+                // itself stays one chain in channel order)
+#pragma unroll 8
                 for (int c = 0; c < s.C; ++c) acc = fmaf(ld(xp + c), ld(wp + c), acc);
             }
         }
