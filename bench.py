@@ -2,7 +2,7 @@
 """Benchmark of the implicit-im2col convolution on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer cfg2] [--eager]
-                    [--no-cpu] [--no-layers] [--no-explicit] [--calibrate]
+                    [--no-cpu] [--no-layers] [--no-explicit] [--calibrate] [--study]
 
 A step is one iconv_fwd call (the whole hot path: tile decomposition, on-the-fly im2col gather,
 MFMA contraction, epilogue) over one batch of seeded synthetic input already resident in device
@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the copy probe on 64 MiB (counter calibration for rocprofv3 --pmc runs)")
     ap.add_argument("--variant", type=int, default=-1, help="force a kernel-table entry (sweeps)")
+    ap.add_argument("--study", action="store_true",
+                    help="add the stride/dilation sensitivity table, the batch 8/64 sweep and the output-type table")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (a batch-sharded forward convolution needs no exchange "
@@ -168,6 +170,44 @@ def main():
             del keep
             torch.cuda.empty_cache()
         out["layers"] = layers
+
+    # ---- studies beyond the headline (off by default; each entry is timed like a layer above) ------
+    if args.study:
+        def quick(Li, code_override=None):
+            c = code_override if code_override is not None else B.DTYPE_CODES[Li.dtype]
+            x, w = workloads.make_inputs(Li)
+            xd, wd = B.to_device(x, c), B.to_device(w, c)
+            y = B.empty_output(Li.N, Li.P, Li.Q, Li.K, c)
+            sa = Li.shape_args()
+            t = time_steps(lambda: B.iconv_fwd(xd, wd, y, *sa, c), 100, 20)
+            del xd, wd, y
+            torch.cuda.empty_cache()
+            return t
+        study = {"stride_dilation": {}, "batch": {}, "output_type": {}}
+        # (1) stride / dilation sensitivity: the convolution against the plain GEMM of the same M x K_gemm x K
+        # shape (a 1x1 convolution over a 1 x 1 x M image with K_gemm channels), as in the paper's stride figure
+        for label, Ls in workloads.study_layers():
+            t_conv = quick(Ls)
+            Lg = workloads.ConvLayer("gemm_" + label, 1, 1, Ls.M, Ls.k_gemm, Ls.K, 1, 1, 1, 0, 1, Ls.dtype, Ls.seed_id + 1)
+            t_gemm = quick(Lg)
+            study["stride_dilation"][label] = {"M": Ls.M, "us": round(t_conv * 1e3, 2), "tflops": round(Ls.flops / t_conv / 1e9, 1),
+                                               "gemm_only_us": round(t_gemm * 1e3, 2),
+                                               "conv_over_gemm_time": round(t_conv / t_gemm, 3)}
+        # (2) batch 8 and 64 for every benchmark layer
+        for name, Li in workloads.LAYERS.items():
+            if name == "cfg1":
+                continue
+            for n in (8, 64):
+                Lb = workloads.with_batch(Li, n)
+                tb = quick(Lb)
+                study["batch"][f"{name}_n{n}"] = {"us": round(tb * 1e3, 2), "tflops": round(Lb.flops_real / tb / 1e9, 1)}
+        # (3) input/output types on the headline layer
+        for tname in ("bf16", "bf16_bf16", "f16", "f16_f16"):
+            Lt = workloads.ConvLayer(L.name, L.N, L.H, L.W, L.C, L.K, L.R, L.S, L.stride, L.pad, L.dilation,
+                                     "f16" if tname.startswith("f16") else "bf16", L.seed_id)
+            tt = quick(Lt, B.DTYPE_CODES[tname])
+            study["output_type"][tname] = {"us": round(tt * 1e3, 2), "tflops": round(L.flops / tt / 1e9, 1)}
+        out["study"] = study
 
     if args.calibrate:
         n = 64 << 20

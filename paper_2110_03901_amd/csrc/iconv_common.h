@@ -45,18 +45,8 @@ template <> struct Elem<f16_t> {
 template <typename O> __device__ __forceinline__ O to_out(float v);
 template <> __device__ __forceinline__ float to_out<float>(float v) { return v; }
 template <> __device__ __forceinline__ f16_t to_out<f16_t>(float v) { return (f16_t)v; }
-template <> __device__ __forceinline__ bf16_t to_out<bf16_t>(float v) {
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7fffffffu) > 0x7f800000u) {          // NaN: keep it a NaN
-        u = (u >> 16) | 0x40u;
-    } else {
-        u = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;  // ties to even
-    }
-    uint16_t h = (uint16_t)u;
-    bf16_t r;
-    __builtin_memcpy(&r, &h, 2);
-    return r;
-}
+// (gfx950 converts in hardware: v_cvt_pk_bf16_f32, round to nearest even, NaN stays NaN)
+template <> __device__ __forceinline__ bf16_t to_out<bf16_t>(float v) { return (bf16_t)v; }
 
 // ---- launchers implemented in the kernel translation units ---------------------------------
 // in/out element codes used by the launch tables

@@ -255,10 +255,12 @@ hipError_t launch_variant(int v, const void* x, const void* w, void* y, const Co
 int choose_variant(const ConvShape& s) {
     const long tiles_256x128 = (long)((s.M + 255) / 256) * ((s.K + 127) / 128);
     const int P0 = kNumVariants;
-    if (s.R * s.S > 1 && s.stride == 1) {
-        // few channels and filters: filters and patch resident in LDS
+    if (s.stride == 1) {
+        // few channels and filters (1x1 layers included): filters and patch resident in LDS
         const int rv = resident_choose(s);
         if (rv >= 0) return P0 + patch_num_variants() + rv;
+    }
+    if (s.R * s.S > 1 && s.stride == 1) {
         int v;
         if (s.K <= 64) v = P0 + 5;                    // p256x64, eight compute waves of 32x64
         else if (tiles_256x128 >= 200) v = P0 + 3;    // p256x128

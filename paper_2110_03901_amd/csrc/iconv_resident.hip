@@ -450,10 +450,14 @@ bool resident_supported(const ConvShape& s, int v) {
 }
 
 // The variant with the lower modelled cost, or -1 when the layer does not fit the kernel.
+// Its blocks are large (448 or 512 pixels x all filters), so it is only offered when there are
+// enough of them to occupy most of the device.
 int resident_choose(const ConvShape& s) {
-    ResGeom g;
+    ResGeom g7, g8;
     double c7 = 0, c8 = 0;
-    const bool ok7 = plan_res(s, 7, &g, &c7), ok8 = plan_res(s, 8, &g, &c8);
+    const long enough = (long)device_cus() * 3 / 4;
+    const bool ok7 = plan_res(s, 7, &g7, &c7) && g7.total_tiles >= enough;
+    const bool ok8 = plan_res(s, 8, &g8, &c8) && g8.total_tiles >= enough;
     if (!ok7 && !ok8) return -1;
     if (ok7 && ok8) return c7 <= c8 ? 0 : 1;
     return ok7 ? 0 : 1;

@@ -69,6 +69,21 @@ def test_benchmark_layer_full_size(B, name):
     check(B, workloads.LAYERS[name])
 
 
+@pytest.mark.parametrize("label", [l for l, _ in workloads.study_layers()])
+def test_stride_dilation_study_shapes(B, label):
+    """The layers of the stride / dilation sensitivity study (strides and dilations 1, 2, 4 of the
+    headline 3x3 layer), at batch 4 so that the oracle stays quick."""
+    L = workloads.with_batch(dict(workloads.study_layers())[label], 4)
+    check(B, L)
+
+
+@pytest.mark.parametrize("name", [n for n in workloads.LAYERS if n != "cfg1"])
+def test_benchmark_layer_at_batch_8(B, name):
+    """Batch 8, one of the paper's two evaluation batch sizes (section 6); cfg5a at batch 4."""
+    L = workloads.LAYERS[name]
+    check(B, workloads.with_batch(L, 4 if name == "cfg5a" else 8))
+
+
 def test_benchmark_layers_need_no_workspace(B):
     for L in workloads.LAYERS.values():
         assert B.iconv_workspace_bytes(B.ALGO_IMPLICIT, *L.shape_args(), code_of(L)) == 0

@@ -134,3 +134,23 @@ def make_inputs(layer: ConvLayer, seed_offset: int = 0):
 
 def small_layer(name, N, H, W, C, K, R, S, stride=1, pad=0, dilation=1, dtype=DT_BF16, seed_id=900):
     return ConvLayer(name, N, H, W, C, K, R, S, stride, pad, dilation, dtype, seed_id)
+
+
+def study_layers():
+    """Shapes of the stride / dilation sensitivity study (the paper's central characterisation,
+    section 3.2 and its stride figure): the headline 3x3 layer at strides 1, 2, 4 and dilations
+    1, 2, 4 ("same" padding = dilation, so the stride alone sets the output size), batch 32.
+    Returns [(label, ConvLayer)]."""
+    base = LAYERS["cfg2"]
+    out = []
+    for stride in (1, 2, 4):
+        for dil in (1, 2, 4):
+            out.append((f"s{stride}_d{dil}", ConvLayer(f"study_s{stride}_d{dil}", base.N, base.H, base.W, base.C, base.K, 3, 3,
+                                                       stride, dil, dil, base.dtype, 600 + 10 * stride + dil)))
+    return out
+
+
+def with_batch(layer, n):
+    """The same layer at another batch size (the paper evaluates at batch 8 and 64, section 6)."""
+    return ConvLayer(f"{layer.name}_n{n}", n, layer.H, layer.W, layer.C, layer.K, layer.R, layer.S, layer.stride, layer.pad,
+                     layer.dilation, layer.dtype, layer.seed_id + 7000 + n, layer.c_real)
