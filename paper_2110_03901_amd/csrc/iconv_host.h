@@ -37,6 +37,19 @@ inline void split_tiles(long total, int cus, int occ, int* per_wg, int* nwg) {
     }
 }
 
+// Resident workgroups per compute unit of `kern` at `lds_bytes` of dynamic LDS, cached per call
+// site in `slot` (initialise it to -1): LDS size and result travel in ONE atomic word, so concurrent
+// callers with different sizes never pair one's size with the other's result.
+inline int cached_occupancy(std::atomic<long long>& slot, const void* kern, int threads, int lds_bytes) {
+    const long long cur = slot.load(std::memory_order_acquire);
+    if (cur >= 0 && (int)(cur >> 8) == lds_bytes) return (int)(cur & 0xff);
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, threads, (size_t)lds_bytes) != hipSuccess || nb < 1) nb = 1;
+    if (nb > 255) nb = 255;
+    slot.store(((long long)lds_bytes << 8) | nb, std::memory_order_release);
+    return nb;
+}
+
 // Cap on the number of workgroups of a persistent launch (0 = none); see iconv_set_max_workgroups.
 extern std::atomic<int> g_max_workgroups;
 

@@ -519,16 +519,8 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
     const long total = (long)s.N * g.tiles_h * g.tiles_w * g.tiles_n;
     if (total > 0x7fffffffL) return hipErrorInvalidConfiguration;
     // resident workgroups per compute unit for this LDS size (cached per kernel and size)
-    static std::atomic<int> occ_lds{-1}, occ_val{1};
-    int occ = occ_val.load(std::memory_order_acquire);
-    if (occ_lds.load(std::memory_order_acquire) != lds_bytes) {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, c.waves() * 64, (size_t)lds_bytes) != hipSuccess || nb < 1)
-            nb = 1;
-        occ = nb;
-        occ_val.store(nb, std::memory_order_release);
-        occ_lds.store(lds_bytes, std::memory_order_release);
-    }
+    static std::atomic<long long> occ_slot{-1};
+    const int occ = cached_occupancy(occ_slot, (const void*)kern, c.waves() * 64, lds_bytes);
     int nwg = 1;
     g.total_tiles = (int)total;
     const int cap = g_max_workgroups.load(std::memory_order_relaxed);

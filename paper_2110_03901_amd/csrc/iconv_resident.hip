@@ -398,16 +398,8 @@ hipError_t launch_res_t(const void* x, const void* w, void* y, const ConvShape& 
         if (e != hipSuccess) return e;
         raised.store(true, std::memory_order_release);
     }
-    static std::atomic<int> occ_lds{-1}, occ_val{1};
-    int occ = occ_val.load(std::memory_order_acquire);
-    if (occ_lds.load(std::memory_order_acquire) != lds_bytes) {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, threads, (size_t)lds_bytes) != hipSuccess || nb < 1)
-            nb = 1;
-        occ = nb;
-        occ_val.store(nb, std::memory_order_release);
-        occ_lds.store(lds_bytes, std::memory_order_release);
-    }
+    static std::atomic<long long> occ_slot{-1};
+    const int occ = cached_occupancy(occ_slot, (const void*)kern, threads, lds_bytes);
     const int cap = g_max_workgroups.load(std::memory_order_relaxed);
     const long slots = cap > 0 ? cap : (long)device_cus() * occ;
     const long per = (g.total_tiles + slots - 1) / slots;

@@ -393,16 +393,8 @@ hipError_t launch_stem_t(const void* x, const void* w, void* y, const ConvShape&
     }
     if (g.tiles_n == 1) {
         // one filter tile: workgroups own ranges of blocks and keep the weights resident
-        static std::atomic<int> occ_lds{-1}, occ_val{1};
-        int occ = occ_val.load(std::memory_order_acquire);
-        if (occ_lds.load(std::memory_order_acquire) != lds_bytes) {
-            int nb = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)kern, threads, (size_t)lds_bytes) != hipSuccess || nb < 1)
-                nb = 1;
-            occ = nb;
-            occ_val.store(nb, std::memory_order_release);
-            occ_lds.store(lds_bytes, std::memory_order_release);
-        }
+        static std::atomic<long long> occ_slot{-1};
+        const int occ = cached_occupancy(occ_slot, (const void*)kern, threads, lds_bytes);
         // The kernel waits on memory most of the time, so every workgroup slot of the device is
         // filled (as many resident workgroups per compute unit as fit), each with an equal range.
         const int cap = g_max_workgroups.load(std::memory_order_relaxed);
