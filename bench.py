@@ -2,7 +2,7 @@
 """Benchmark of the implicit-im2col convolution on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer cfg2] [--eager]
-                    [--no-cpu] [--no-layers] [--no-explicit] [--calibrate] [--study]
+                    [--no-cpu] [--no-layers] [--no-explicit] [--no-probes] [--calibrate] [--study]
 
 A step is one iconv_fwd call (the whole hot path: tile decomposition, on-the-fly im2col gather,
 MFMA contraction, epilogue) over one batch of seeded synthetic input already resident in device
@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-explicit", action="store_true", help="skip the explicit im2col + GEMM comparison")
+    ap.add_argument("--no-probes", action="store_true", help="skip the achievable-rate probes (MFMA loop, copy)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the copy probe on 64 MiB (counter calibration for rocprofv3 --pmc runs)")
     ap.add_argument("--variant", type=int, default=-1, help="force a kernel-table entry (sweeps)")
@@ -208,6 +209,23 @@ def main():
             tt = quick(Lt, B.DTYPE_CODES[tname])
             study["output_type"][tname] = {"us": round(tt * 1e3, 2), "tflops": round(L.flops / tt / 1e9, 1)}
         out["study"] = study
+
+    # ---- achievable rates on this machine: register-only MFMA loop and a large device copy ----------
+    if not args.no_probes:
+        iters = 2000
+        pout = torch.empty(B.MFMA_PROBE_GROUPS * 256, dtype=torch.float32, device="cuda:0")
+        t_m = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters), 20, 3)
+        probe_tflops = B.MFMA_PROBE_GROUPS * 4 * iters * 8 * 32768 / (t_m * 1e-3) / 1e12
+        nb = 256 << 20
+        a = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+        t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3)
+        out["achievable"] = {"mfma_bf16_tflops": round(probe_tflops, 1),
+                             "mfma_frac_of_datasheet": round(probe_tflops / PEAK_MFMA_TFLOPS, 4),
+                             "copy_gbs_read_plus_write": round(2 * nb / (t_c * 1e-3) / 1e9, 1),
+                             "value_frac_of_achievable_mfma": round(tflops / probe_tflops, 4)}
+        del a, b, pout
+        torch.cuda.empty_cache()
 
     if args.calibrate:
         n = 64 << 20

@@ -99,6 +99,13 @@ int iconv_im2col(const void *x_nhwc, void *workspace, size_t workspace_bytes,
  * the achievable copy bandwidth. */
 int iconv_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* Measurement helper: a register-only loop of `iters` x 8 bf16 32x32x16 MFMAs per wave on
+ * 1024 workgroups of four waves (no memory traffic in the loop), for the achievable matrix-core
+ * rate: 1024 * 4 * iters * 8 * 32768 flop per launch.  `out` is a device buffer of at least
+ * 1024 * 256 * 4 bytes that receives one float per thread (so that the loop is not optimised
+ * away).  Returns ICONV_ERR_NULL, ICONV_ERR_SHAPE (iters < 1), ICONV_ERR_WORKSPACE (out too small). */
+int iconv_probe_mfma(void *out, size_t out_bytes, int iters, void *stream);
+
 /* Tile-selection override for sweeps: -1 (default) lets the library choose, other values pick
  * entry `variant` of the kernel table (see iconv_variant_name).  Process-wide, not
  * thread-safe; meant for benchmarking only.  Returns ICONV_ERR_UNSUPPORTED if out of range. */

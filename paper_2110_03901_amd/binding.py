@@ -41,6 +41,8 @@ _lib.iconv_im2col.restype = _i
 _lib.iconv_im2col.argtypes = [_p, _p, _sz] + [_i] * 10 + [_p]
 _lib.iconv_probe_copy.restype = _i
 _lib.iconv_probe_copy.argtypes = [_p, _p, _sz, _p]
+_lib.iconv_probe_mfma.restype = _i
+_lib.iconv_probe_mfma.argtypes = [_p, _sz, _i, _p]
 _lib.iconv_set_variant.restype = _i
 _lib.iconv_set_variant.argtypes = [_i]
 _lib.iconv_set_max_workgroups.restype = _i
@@ -52,7 +54,7 @@ _lib.iconv_status_string.restype = ctypes.c_char_p
 _lib.iconv_status_string.argtypes = [_i]
 
 EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
-           "iconv_probe_copy", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name",
+           "iconv_probe_copy", "iconv_probe_mfma", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name",
            "iconv_status_string"]
 
 
@@ -129,6 +131,15 @@ def iconv_im2col(x, workspace, workspace_bytes, N, H, W, C, R, S, stride, pad, d
 
 def iconv_probe_copy(dst, src, nbytes, stream=None) -> None:
     rc = _lib.iconv_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream))
+    if rc != 0:
+        raise IconvError(rc)
+
+
+MFMA_PROBE_GROUPS = 1024
+
+
+def iconv_probe_mfma(out, out_bytes, iters, stream=None) -> None:
+    rc = _lib.iconv_probe_mfma(_ptr(out), out_bytes, iters, _stream(stream))
     if rc != 0:
         raise IconvError(rc)
 

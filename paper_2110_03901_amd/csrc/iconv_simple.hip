@@ -71,6 +71,31 @@ __global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride_t) dst[i] = src[i];
 }
 
+// Register-only MFMA loop: eight independent accumulator tiles per wave, operands never reloaded.
+__global__ void __launch_bounds__(256) mfma_probe_kernel(float* __restrict__ out, int iters) {
+    floatx16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    bf16x8 a, b;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        a[j] = (bf16_t)(float)((threadIdx.x + j) & 7);
+        b[j] = (bf16_t)(float)(j + 1);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[i][v];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
 int grid_for(long long total, int block) {
     long long g = (total + block - 1) / block;
     const long long cap = 256LL * 64;  // grid-stride beyond this
@@ -131,6 +156,11 @@ hipError_t launch_im2col(const void* x, void* low, const ConvShape& s, int elt_b
         hipLaunchKernelGGL((im2col_kernel<uint16_t, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st,
                            (const uint16_t*)x, (uint16_t*)low, s);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_probe(void* out, int iters, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(kMfmaProbeGroups), dim3(256), 0, st, (float*)out, iters);
     return hipGetLastError();
 }
 

@@ -330,3 +330,25 @@ def test_error_returns_on_device_pointers(B):
     assert B.iconv_fwd_explicit_raw(xd, wd, y, None, 0, *L.shape_args(), 0) == -5
     with pytest.raises(B.IconvError):
         B.iconv_fwd(xd, wd, y, 1, 8, 8, 16, 16, 9, 9, 1, 0, 1, 0)
+
+
+def test_probes_run_and_are_exact(B):
+    """The two measurement helpers: the copy probe copies, and one iteration of the MFMA probe
+    gives the product of its fixed operands (A[m][k] = (m + k) mod 8, B[k][n] = k mod 8 + 1)."""
+    n = 1 << 20
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros_like(src)
+    B.iconv_probe_copy(dst, src, n)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    out = torch.full((B.MFMA_PROBE_GROUPS * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
+    B.iconv_probe_mfma(out, out.numel() * 4, 1)
+    torch.cuda.synchronize()
+    m, k = np.arange(32)[:, None], np.arange(16)[None, :]
+    A = ((m + k) % 8).astype(np.float64)
+    Bm = np.tile((np.arange(16) % 8 + 1.0)[:, None], (1, 32))
+    total_per_wave = 8 * (A @ Bm).sum()            # eight accumulator tiles per wave
+    got = out.double().view(-1, 64).sum(dim=1).cpu().numpy()
+    assert np.array_equal(got, np.full_like(got, total_per_wave))
+    with pytest.raises(B.IconvError):
+        B.iconv_probe_mfma(out, 16, 1)
