@@ -214,14 +214,18 @@ def main():
     if not args.no_probes:
         iters = 2000
         pout = torch.empty(B.MFMA_PROBE_GROUPS * 256, dtype=torch.float32, device="cuda:0")
+        probe_flop = B.MFMA_PROBE_GROUPS * 4 * iters * 8 * 32768
         t_m = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters), 20, 3)
-        probe_tflops = B.MFMA_PROBE_GROUPS * 4 * iters * 8 * 32768 / (t_m * 1e-3) / 1e12
+        probe_tflops = probe_flop / (t_m * 1e-3) / 1e12
+        t_r = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters, True), 20, 3)
+        probe_random = probe_flop / (t_r * 1e-3) / 1e12
         nb = 256 << 20
         a = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
         b = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
         t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3)
         out["achievable"] = {"mfma_bf16_tflops": round(probe_tflops, 1),
                              "mfma_frac_of_datasheet": round(probe_tflops / PEAK_MFMA_TFLOPS, 4),
+                             "mfma_bf16_tflops_random_operands": round(probe_random, 1),
                              "copy_gbs_read_plus_write": round(2 * nb / (t_c * 1e-3) / 1e9, 1),
                              "value_frac_of_achievable_mfma": round(tflops / probe_tflops, 4)}
         del a, b, pout

@@ -101,10 +101,13 @@ int iconv_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* Measurement helper: a register-only loop of `iters` x 8 bf16 32x32x16 MFMAs per wave on
  * 1024 workgroups of four waves (no memory traffic in the loop), for the achievable matrix-core
- * rate: 1024 * 4 * iters * 8 * 32768 flop per launch.  `out` is a device buffer of at least
+ * rate: 1024 * 4 * iters * 8 * 32768 flop per launch.  random_operands = 0 multiplies one fixed
+ * pair of small-integer operands (few bits toggle, the highest clock the chip sustains);
+ * random_operands != 0 alternates four pairs of pseudo-random operands, the rate the matrix cores
+ * sustain on real data under the board's power limit.  `out` is a device buffer of at least
  * 1024 * 256 * 4 bytes that receives one float per thread (so that the loop is not optimised
  * away).  Returns ICONV_ERR_NULL, ICONV_ERR_SHAPE (iters < 1), ICONV_ERR_WORKSPACE (out too small). */
-int iconv_probe_mfma(void *out, size_t out_bytes, int iters, void *stream);
+int iconv_probe_mfma(void *out, size_t out_bytes, int iters, int random_operands, void *stream);
 
 /* Tile-selection override for sweeps: -1 (default) lets the library choose, other values pick
  * entry `variant` of the kernel table (see iconv_variant_name).  Process-wide, not

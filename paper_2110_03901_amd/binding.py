@@ -42,7 +42,7 @@ _lib.iconv_im2col.argtypes = [_p, _p, _sz] + [_i] * 10 + [_p]
 _lib.iconv_probe_copy.restype = _i
 _lib.iconv_probe_copy.argtypes = [_p, _p, _sz, _p]
 _lib.iconv_probe_mfma.restype = _i
-_lib.iconv_probe_mfma.argtypes = [_p, _sz, _i, _p]
+_lib.iconv_probe_mfma.argtypes = [_p, _sz, _i, _i, _p]
 _lib.iconv_set_variant.restype = _i
 _lib.iconv_set_variant.argtypes = [_i]
 _lib.iconv_set_max_workgroups.restype = _i
@@ -138,8 +138,8 @@ def iconv_probe_copy(dst, src, nbytes, stream=None) -> None:
 MFMA_PROBE_GROUPS = 1024
 
 
-def iconv_probe_mfma(out, out_bytes, iters, stream=None) -> None:
-    rc = _lib.iconv_probe_mfma(_ptr(out), out_bytes, iters, _stream(stream))
+def iconv_probe_mfma(out, out_bytes, iters, random_operands=False, stream=None) -> None:
+    rc = _lib.iconv_probe_mfma(_ptr(out), out_bytes, iters, int(bool(random_operands)), _stream(stream))
     if rc != 0:
         raise IconvError(rc)
 

@@ -142,12 +142,12 @@ int iconv_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
     return status_of(launch_copy(dst, src, bytes, (hipStream_t)stream));
 }
 
-int iconv_probe_mfma(void* out, size_t out_bytes, int iters, void* stream) {
+int iconv_probe_mfma(void* out, size_t out_bytes, int iters, int random_operands, void* stream) {
     if (!out) return ICONV_ERR_NULL;
     if (iters < 1) return ICONV_ERR_SHAPE;
     if (out_bytes < (size_t)kMfmaProbeGroups * 256 * sizeof(float)) return ICONV_ERR_WORKSPACE;
     if (!aligned16(out)) return ICONV_ERR_ALIGN;
-    return status_of(launch_mfma_probe(out, iters, (hipStream_t)stream));
+    return status_of(launch_mfma_probe(out, iters, random_operands != 0, (hipStream_t)stream));
 }
 
 int iconv_set_variant(int variant) {

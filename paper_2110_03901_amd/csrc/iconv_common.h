@@ -87,6 +87,6 @@ hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s
 hipError_t launch_im2col(const void* x, void* lowered, const ConvShape& s, int elt_bytes, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 constexpr int kMfmaProbeGroups = 1024;   // workgroups of the MFMA probe (four per compute unit)
-hipError_t launch_mfma_probe(void* out, int iters, hipStream_t stream);
+hipError_t launch_mfma_probe(void* out, int iters, bool random_operands, hipStream_t stream);
 
 }  // namespace iconv

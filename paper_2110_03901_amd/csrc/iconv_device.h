@@ -92,4 +92,53 @@ template <> __device__ __forceinline__ void store_piece<f16_t>(u32x4 v, rsrc_t r
     __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, h), rsrc, (int)off, 0, 0);
 }
 
+// Bytes of wave-private LDS one call of store_frag_staged needs.
+constexpr int kFragStageBytes = 2048;
+
+// Writes one 32 x 32 accumulator fragment of the MFMA kernels to y through a wave-private LDS
+// staging area, so that every store instruction covers whole 128-byte lines of y rows.  In the
+// fragment lane l holds pixel l%32 and, in element v, filter 8*(v/4) + 4*(l/32) + v%4; written
+// directly, one store instruction would touch 32 rows with 32 bytes each.  Half a fragment (16
+// pixels x 32 filters, 2 KiB) goes through the staging area at a time: piece c (16 bytes, four
+// filters) of pixel i sits at i*128 + ((c ^ ((i >> 1) & 7)) << 4), which keeps both the deposit
+// (16 pixels x 2 pieces per instruction) and the row-wise read-back free of bank conflicts.  The
+// read-back gives lane l piece l%8 of pixels l/8 and l/8 + 8 of the half: eight lanes = one line.
+// `row_off(i)` returns the byte offset, within the buffer of `y_rsrc`, of the first of the
+// fragment's 32 filters in the y row of fragment pixel i, or an offset that the piece offset
+// cannot bring back into range (e.g. 0x80000000 with fewer than 2^31 bytes in the buffer) to drop
+// the pixel.  `pieces_ok` says whether this lane's four filters (piece l%8) exist.  `stg` is the
+// wave's own staging area; LDS operations of one wave complete in order, so no wait is needed
+// between the halves.
+template <typename TO, typename RowOff>
+__device__ __forceinline__ void store_frag_staged(char* stg, const floatx16& acc, int lane, rsrc_t y_rsrc, bool pieces_ok,
+                                                  RowOff row_off) {
+    const int frow = lane & 31, fk = lane >> 5, f16 = frow & 15;
+    const int l8 = lane >> 3, c8 = lane & 7;
+    const uint32_t sw0 = (uint32_t)(f16 * 128 + ((fk ^ ((f16 >> 1) & 7)) << 4));         // piece 2*gq + fk: xor (gq << 5)
+    const uint32_t sr0 = (uint32_t)(l8 * 128 + ((c8 ^ ((l8 >> 1) & 7)) << 4));
+    const uint32_t sr1 = (uint32_t)((l8 + 8) * 128 + ((c8 ^ (((l8 + 8) >> 1) & 7)) << 4));
+    u32x4 out[2][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        __builtin_amdgcn_wave_barrier();
+        if ((frow >> 4) == h) {
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                floatx4 v = {acc[4 * gq], acc[4 * gq + 1], acc[4 * gq + 2], acc[4 * gq + 3]};
+                *reinterpret_cast<floatx4*>(stg + (sw0 ^ (uint32_t)(gq << 5))) = v;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        out[h][0] = *reinterpret_cast<const u32x4*>(stg + sr0);
+        out[h][1] = *reinterpret_cast<const u32x4*>(stg + sr1);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t ro = row_off(h * 16 + 8 * j + l8);
+            if (pieces_ok) store_piece<TO>(out[h][j], y_rsrc, ro + (uint32_t)(4 * c8) * (uint32_t)sizeof(TO));
+        }
+}
+
 }  // namespace iconv

@@ -167,6 +167,34 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
     }
     wait_vmcnt<0>();                            // drain the trailing no-op loads before the wave ends
 
+    // ---- epilogue through LDS (whole 128-byte lines per store) when y rows are made of 16-byte
+    // pieces and the tile's offsets fit the 32-bit buffer offset; the stages are free once every
+    // wave has left the K loop.
+    if ((s.K & 3) == 0 && (long long)s.K * BM * (long long)sizeof(TO) < 0x7fffffffLL) {
+        __syncthreads();
+        char* stg = reinterpret_cast<char*>(lds) + wave * kFragStageBytes;
+        static_assert(WAVES * kFragStageBytes <= ST * STAGE_CHUNKS * 16, "staging must fit the stages");
+        const size_t org = (size_t)m0 * s.K;
+        const size_t rem = ((size_t)s.M * s.K - org) * sizeof(TO);
+        // at most 2^31 - 1 bytes in range, so that the drop marker below stays out of range
+        const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0x7fffffffull ? 0x7fffffffu : (uint32_t)rem,
+                                                               kRsrcFlags);
+        const int rows_left = s.M - m0;         // rows of this tile that exist
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int col0 = k0 + wave_n * WN + ni * 32;
+                const int row0 = wave_m * WM + mi * 32;
+                const bool pieces_ok = col0 + 4 * (lane & 7) + 3 < s.K;
+                store_frag_staged<TO>(stg, acc[mi][ni], lane, y_rsrc, pieces_ok, [&](int i) {
+                    const int row = row0 + i;
+                    return row < rows_left ? (uint32_t)(row * s.K + col0) * (uint32_t)sizeof(TO) : 0x80000000u;
+                });
+            }
+        return;
+    }
+
     // ---- epilogue.  The filter fragment is the MFMA's row operand and the pixel fragment its
     // column operand, so lane l holds output row (pixel) l%32 of the 32-row block and, in
     // accumulator element v, filter 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block: four
@@ -228,7 +256,13 @@ hipError_t launch_dma(const void* x, const void* w, void* y, const ConvShape& s,
     X(4, "d256x256x32_w128x64_s3", (launch_dma<T, TO, 256, 256, 32, 128, 64, 3>)) \
     X(5, "d64x64x64_w32x32_s4", (launch_dma<T, TO, 64, 64, 64, 32, 32, 4>))       \
     X(6, "d128x128x64_w64x32_s3", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3>))   \
-    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))
+    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))     \
+    X(8, "d128x128x64_w64x64_s5", (launch_dma<T, TO, 128, 128, 64, 64, 64, 5>))   \
+    X(9, "d128x128x64_w64x64_s4", (launch_dma<T, TO, 128, 128, 64, 64, 64, 4>))   \
+    X(10, "d128x128x32_w64x64_s8", (launch_dma<T, TO, 128, 128, 32, 64, 64, 8>))  \
+    X(11, "d256x256x32_w128x64_s5", (launch_dma<T, TO, 256, 256, 32, 128, 64, 5>)) \
+    X(12, "d128x64x64_w64x32_s6", (launch_dma<T, TO, 128, 64, 64, 64, 32, 6>))    \
+    X(13, "d256x128x32_w64x64_s6", (launch_dma<T, TO, 256, 128, 32, 64, 64, 6>))
 
 #define X_NAME(i, name, fn) name,
 const char* const kVariantNames[] = {ICONV_VARIANTS(X_NAME)};

@@ -80,10 +80,13 @@ template <int BN> __device__ __forceinline__ TileCoord decode_tile(int t, const 
     return c;
 }
 
-template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW>
-__global__ void __launch_bounds__((WAVES_M * WAVES_N + NLD + NSW) * 64)
+template <int V> struct IntTag { static constexpr int value = V; };
+
+template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
+          int KS, int PF>
+__global__ void __launch_bounds__((WAVES_M * WAVES_N * KS + NLD + NSW) * 64)
 ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const PatchGeom g) {
-    constexpr int WAVES_C = WAVES_M * WAVES_N;  // compute waves
+    constexpr int WAVES_C = WAVES_M * WAVES_N * KS;  // compute waves
     constexpr int CPR = CB / 8;                 // 16-byte chunks per pixel (or filter row) and channel chunk
     constexpr int RPB = 64 / CPR;               // pixels (filter rows) one wave-wide load covers
     constexpr int PPW = 16 / CPR;               // pixels per 256-byte LDS window
@@ -99,6 +102,15 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     constexpr int ST_ROWS = 64 / SPR;           // staging rows one wave-wide store covers
     constexpr int ST_IT = SS > 0 ? BM / ST_ROWS / (NSW > 0 ? NSW : 1) : 0;   // wave-wide stores per store wave per tile
     static_assert((STB - 2) * B_IT + (STB - 1) * LA < 64, "too many loads in flight for vmcnt");
+    static_assert(KS >= 1 && KI % KS == 0 && (MI * NI) % KS == 0, "K slices and fragments must divide over the K-split waves");
+    static_assert(PF == 0 || (STB >= 3 && SS == 0), "the prefetching pipeline needs three filter stages and stores its own output");
+    static_assert(KS == 1 || PF == 1, "K-split waves are built on the prefetching pipeline only");
+    // Steady-state loads that may stay in flight when a step's barrier is reached.  Without
+    // prefetch the step's own filter tile must have landed; with prefetch (PF) the NEXT step's must.
+    constexpr int WAIT_STEP = PF ? (STB - 3) * B_IT + (STB - 2) * LA : (STB - 2) * B_IT + (STB - 1) * LA;
+    // K-split reduction: per round every wave hands KS-1 fragments (4 KiB each) to their owners
+    constexpr int RED_ROUNDS = KS > 1 ? (MI * NI) / KS : 0;
+    constexpr int RED_BARRIERS = KS > 1 ? 2 * RED_ROUNDS - 1 : 0;
     static_assert((SS == 0 && NSW == 0) || (SS > 0 && NSW > 0 && BM % (ST_ROWS * NSW) == 0 && SPR <= 64),
                   "staging rows must divide over the store waves");
     typedef typename Elem<T>::frag frag_t;
@@ -118,7 +130,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     const int phases = (t_end - t_begin) * chunks;           // (tile, channel chunk) pairs of this workgroup
     const int steps = phases * RS;
     const uint32_t bstage_off = 2u * (uint32_t)g.patch_bytes;   // byte offset of the filter ring
-    const uint32_t staging_off = bstage_off + STB * BSTAGE_BYTES + NLD * 1024;   // byte offset of the staging buffer
+    const uint32_t staging_off = bstage_off + STB * BSTAGE_BYTES + NLD * 1024;   // byte offset of the staging buffer (SS > 0) or of the K-split exchange area (KS > 1)
     const int steps_per_tile = chunks * RS;
     // which bits of the window number the patch swizzle XORs into the slot number (see above)
     const int wmask = (s.stride & 1) ? (CPR - 1) : 15;
@@ -159,7 +171,8 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 a_n = tc.n;
                 a_hb = tc.p0 * s.stride - s.pad;
                 a_wb = tc.q0 * s.stride - s.pad;
-                a_c0 = (phase % chunks) * CB;
+                const int ck = phase % chunks + (t_begin + phase / chunks) % chunks;   // rotated chunk order, see filter_load
+                a_c0 = (ck >= chunks ? ck - chunks : ck) * CB;
                 a_buf = phase & 1;
             }
         };
@@ -196,7 +209,14 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             }
         };
         filter_tile();
-        int lr_ = 0, ls_ = 0, lc0 = 0;          // tap (lr_, ls_) of channel chunk lc0 to load next
+        // Tap (lr_, ls_) of channel chunk lc0 is loaded next.  Tile t walks its channel chunks in the
+        // rotated order (t % chunks), (t % chunks) + 1, ..., wrapping around (the order of summation is
+        // free, section 3.2): workgroups that run side by side then read different chunks at any
+        // moment.  With one common order they would all fetch the same 16-byte column range of every
+        // filter row at once, addresses that differ by multiples of the row length and land on few
+        // memory channels.
+        int lr_ = 0, ls_ = 0, lck = 0, lrot = t_begin % chunks;
+        int lc0 = lrot * CB;
         auto filter_load = [&](int stage, bool live) {
             const uint32_t delta = (uint32_t)((lr_ * s.S + ls_) * s.C + lc0) * 2u;     // tap and chunk: uniform
             if (!live) {
@@ -223,11 +243,13 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 ls_ = 0;
                 if (++lr_ == s.R) {
                     lr_ = 0;
-                    lc0 += CB;
-                    if (lc0 >= s.C) {           // next tile
-                        lc0 = 0;
+                    if (++lck == chunks) {      // next tile
+                        lck = 0;
                         if (++b_tile < t_end) filter_tile();
+                        lrot = b_tile % chunks;
                     }
+                    const int ck = lck + lrot;
+                    lc0 = (ck >= chunks ? ck - chunks : ck) * CB;
                 }
             }
         };
@@ -244,21 +266,34 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 #pragma unroll
             for (int l = 0; l < LA; ++l) dma16(x_rsrc, x_bytes, sink);
         }
-        int fill = STB - 1, step = 0;
+        if (PF) {
+            // the compute waves read the first step's operands before the loop: stage 0 and patch 0
+            wait_vmcnt<(STB - 2) * B_IT + (STB - 1) * LA>();
+            __syncthreads();
+        }
+        int fill = STB - 1, step = 0, tile_step = 0;
         for (int phase = 0; phase < phases; ++phase) {
             patch_begin(phase + 1);
             for (int t = 0; t < RS; ++t, ++step) {
-                // Everything issued after this step's filter tile may stay in flight: STB-2 later
-                // filter tiles and STB-1 groups of patch loads.
-                wait_vmcnt<(STB - 2) * B_IT + (STB - 1) * LA>();
+                // Everything issued after the filter tile that has to be complete may stay in flight
+                // (without prefetch: STB-2 later filter tiles and STB-1 groups of patch loads).
+                wait_vmcnt<WAIT_STEP>();
                 __syncthreads();
+                // The stage refilled here was read for the last time before the barrier just passed:
+                // in step - 1, with prefetch partly in step - 2.
                 filter_load(fill, step + STB - 1 < steps);
                 // The next phase's patch arrives LA loads per step; the last STB-1 steps of a phase
                 // carry no-op loads only, so the patch is complete once the next phase's first step
-                // has waited.
+                // has waited (with prefetch: once the phase's last step has, which reads ahead).
 #pragma unroll
                 for (int l = 0; l < LA; ++l) patch_load(t <= RS - STB);
                 fill = fill + 1 == STB ? 0 : fill + 1;
+                if (KS > 1 && ++tile_step == steps_per_tile) {
+                    // the compute waves' exchange of partial sums at the end of a tile
+                    tile_step = 0;
+#pragma unroll
+                    for (int b = 0; b < RED_BARRIERS; ++b) __syncthreads();
+                }
             }
         }
         wait_vmcnt<0>();
@@ -315,7 +350,8 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     }
 
     // =============================== compute waves ==============================================
-    const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+    const int ks = wave % KS, pos = wave / KS;  // K-split index and tile position of this wave
+    const int wave_m = pos / WAVES_N, wave_n = pos % WAVES_N;
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.TH * g.TW;
     int a_base[MI];                             // patch pixel of each A-fragment row at tap (0, 0)
@@ -337,6 +373,217 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         for (int kk = 0; kk < KI; ++kk) b_idx[ni][kk] = row * CPR + swz<CPR>(row, kk * 2 + fk);
     }
     const bool vec_ok = (s.K & 3) == 0;
+
+    // Epilogue of one tile for the fragments this wave owns.  The filter fragment is the MFMA's row
+    // operand and the pixel fragment its column operand, so lane l holds block pixel 32*frag + l%32
+    // and, in accumulator element v, filter 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block: four
+    // consecutive filters per group of four elements, stored as one 16-byte (fp32) or 8-byte
+    // (16-bit) piece of the pixel's y row.  The stores are not waited for.
+    auto store_tile = [&](int tile, floatx16 (&acc)[MI][NI]) __attribute__((always_inline)) {
+        const TileCoord tc = decode_tile<BN>(tile, g);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
+            if (p < s.P && q < s.Q) {
+                TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    if (KS > 1 && (mi * NI + ni) % KS != ks) continue;      // another wave's fragment
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int col = tc.k0 + (wave_n * NI + ni) * 32 + 8 * gq + 4 * fk;
+                        if (vec_ok && col + 3 < s.K) {
+                            store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
+                                       acc[mi][ni][4 * gq + 3]);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    if constexpr (PF != 0) {
+        // ---- prefetching pipeline.  The wave's K slices of a step (slices ks, ks + KS, ... of the
+        // chunk) form KG groups of KPG slices.  The operands of group g + 1 are read from LDS
+        // before the MFMAs of group g are issued, across step boundaries too: the first group of
+        // step i + 1 is read during step i.  The matrix pipe therefore never waits for an LDS read
+        // after a barrier; in return the loaders keep one more filter stage complete.
+        constexpr int KIW = KI / KS;                // K slices of this wave per step
+        constexpr int KPG = KIW >= 4 ? 2 : 1;       // slices per group
+        constexpr int KG = KIW / KPG;               // groups per step
+        int kx[KIW];                                // chunk-index XOR term of each of the wave's slices
+#pragma unroll
+        for (int j = 0; j < KIW; ++j) kx[j] = (ks + KS * j) * 2;
+        int b_own[NI][KIW];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int row = (wave_n * NI + ni) * 32 + frow;
+#pragma unroll
+            for (int j = 0; j < KIW; ++j) b_own[ni][j] = row * CPR + swz<CPR>(row, kx[j] + fk);
+        }
+        // read cursor: the step whose operands are fetched next
+        int r_stage = 0, r_phase = 0, r_tr = 0, r_ts = 0;
+        int a_win[MI], a_sx[MI];
+        const u32x4* Bt = lds;
+        auto point = [&]() __attribute__((always_inline)) {                        // operand addresses of the cursor's step
+            const uint32_t patch_cur = (uint32_t)(r_phase & 1) * (g.patch_bytes >> 4);
+            const int tap_off = (r_tr * g.PW + r_ts) * s.dil;
+            Bt = lds + ((bstage_off + r_stage * BSTAGE_BYTES) >> 4);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int pp = a_base[mi] + tap_off;
+                a_win[mi] = patch_cur + (pp / PPW) * 16;
+                a_sx[mi] = ((pp % PPW) * CPR + fk) ^ ((pp / PPW) & wmask);
+            }
+        };
+        auto advance = [&]() __attribute__((always_inline)) {      // branch-free: the step stays one scheduling region
+            r_stage = r_stage + 1 == STB ? 0 : r_stage + 1;
+            const int ts = r_ts + 1;
+            const int wrap_s = ts == s.S ? 1 : 0;
+            r_ts = wrap_s ? 0 : ts;
+            const int tr = r_tr + wrap_s;
+            const int wrap_r = tr == s.R ? 1 : 0;
+            r_tr = wrap_r ? 0 : tr;
+            r_phase += wrap_r;
+        };
+        frag_t af[2][KPG][MI], bfr[2][KPG][NI];
+        auto read_group = [&](auto GK, auto BUF) __attribute__((always_inline)) {  // group GK of the cursor's step into register buffer BUF
+            constexpr int gk = decltype(GK)::value, buf = decltype(BUF)::value;
+#pragma unroll
+            for (int k2 = 0; k2 < KPG; ++k2) {
+                constexpr int j0 = gk * KPG;
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+                    af[buf][k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ kx[j0 + k2])]);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) bfr[buf][k2][ni] = __builtin_bit_cast(frag_t, Bt[b_own[ni][j0 + k2]]);
+            }
+        };
+
+        floatx16 acc[MI][NI];
+        auto clear_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+        };
+        // End of a tile.  With K-split waves the KS partial sums of every fragment meet at the
+        // fragment's owner (fragment f belongs to wave f % KS of its position) through an exchange
+        // area in LDS: per round each wave deposits the KS-1 fragments of that round it does not own
+        // (lane-linear 16-byte pieces), one barrier, the owner adds them in a fixed order.
+        auto finish_tile = [&](int tile) __attribute__((always_inline)) {
+            if constexpr (KS > 1) {
+                u32x4* red = lds + (staging_off >> 4) + pos * (KS * (KS - 1) * 256);
+#pragma unroll
+                for (int rd = 0; rd < RED_ROUNDS; ++rd) {
+#pragma unroll
+                    for (int fl = 0; fl < KS; ++fl) {
+                        const int f = rd * KS + fl;
+                        if (ks != fl) {
+                            const int src = ks > fl ? ks - 1 : ks;
+                            u32x4* dst = red + (fl * (KS - 1) + src) * 256 + lane;
+#pragma unroll
+                            for (int v4 = 0; v4 < 4; ++v4) {
+                                floatx4 v = {acc[f / NI][f % NI][4 * v4], acc[f / NI][f % NI][4 * v4 + 1],
+                                             acc[f / NI][f % NI][4 * v4 + 2], acc[f / NI][f % NI][4 * v4 + 3]};
+                                dst[v4 * 64] = __builtin_bit_cast(u32x4, v);
+                            }
+                        }
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int fl = 0; fl < KS; ++fl) {
+                        const int f = rd * KS + fl;
+                        if (ks == fl) {
+#pragma unroll
+                            for (int src = 0; src < KS - 1; ++src) {
+                                const u32x4* from = red + (fl * (KS - 1) + src) * 256 + lane;
+#pragma unroll
+                                for (int v4 = 0; v4 < 4; ++v4) {
+                                    const floatx4 v = __builtin_bit_cast(floatx4, from[v4 * 64]);
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) acc[f / NI][f % NI][4 * v4 + e] += v[e];
+                                }
+                            }
+                        }
+                    }
+                    if (rd != RED_ROUNDS - 1) __syncthreads();
+                }
+            }
+            store_tile(tile, acc);
+        };
+
+        int tile = t_begin, tile_step = 0;
+        auto one_step = [&](auto PAR) __attribute__((always_inline)) {             // PAR: register buffer that holds this step's first group
+            constexpr int par = decltype(PAR)::value;
+            __syncthreads();                        // the NEXT step's filter tile (and patch) has landed
+            {
+                // (the group number is a type: the register buffers must be indexed by constants)
+                auto body = [&](auto GKT) __attribute__((always_inline)) {
+                    constexpr int g0 = decltype(GKT)::value;
+                    constexpr int cur = (par + g0) & 1, nxt = cur ^ 1;
+                    if constexpr (g0 == KG - 1) {
+                        advance();
+                        point();
+                        read_group(IntTag<0>{}, IntTag<nxt>{});
+                    } else {
+                        read_group(IntTag<g0 + 1>{}, IntTag<nxt>{});
+                    }
+#pragma unroll
+                    for (int k2 = 0; k2 < KPG; ++k2)
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                            for (int ni = 0; ni < NI; ++ni)
+                                acc[mi][ni] = Elem<T>::mfma32(bfr[cur][k2][ni], af[cur][k2][mi], acc[mi][ni]);
+                    // Issue order within the group: one MFMA, then the address arithmetic and LDS reads
+                    // of the next group that fit into the 32 cycles the matrix pipe works on it.  A wave
+                    // issues in order, so only instructions placed BETWEEN its MFMAs overlap with them.
+                    constexpr int NM = KPG * MI * NI, NR = KPG * (MI + NI);
+                    constexpr int RPM = (NR + NM - 1) / NM;
+#pragma unroll
+                    for (int i = 0; i < NM; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);      // VALU
+                        __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);    // LDS read
+                    }
+                };
+                body(IntTag<0>{});
+                if constexpr (KG > 1) body(IntTag<1>{});
+                if constexpr (KG > 2) body(IntTag<2>{});
+                if constexpr (KG > 3) body(IntTag<3>{});
+            }
+            if (++tile_step == steps_per_tile) {
+                finish_tile(tile);
+                tile_step = 0;
+                ++tile;
+                clear_acc();
+            }
+        };
+        static_assert(KG >= 1 && KG <= 4, "at most four groups per step");
+
+        clear_acc();
+        __syncthreads();                            // stage 0 and the first patch have landed
+        point();
+        read_group(IntTag<0>{}, IntTag<0>{});
+        for (int step = 0; step < steps;) {
+            one_step(IntTag<0>{});
+            ++step;
+            if constexpr ((KG & 1) != 0) {          // an odd number of groups flips the buffer parity per step
+                if (step < steps) {
+                    one_step(IntTag<1>{});
+                    ++step;
+                }
+            }
+        }
+        return;
+    }
 
     int stage = 0, phase = 0;
     for (int tile = t_begin; tile < t_end; ++tile) {
@@ -394,11 +641,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             }
         }
 
-        // ---- the tile's epilogue.  The filter fragment is the MFMA's row operand and the pixel
-        // fragment its column operand, so lane l holds block pixel 32*frag + l%32 and, in
-        // accumulator element v, filter 8*(v/4) + 4*(l/32) + v%4 of the 32-wide block: four
-        // consecutive filters per group of four elements, stored as one 16-byte (fp32) or 8-byte
-        // (16-bit) piece of the pixel's y row.  The stores are not waited for.
+        // ---- the tile's epilogue: into the staging buffer for the store waves, or straight to y
         if (SS > 0) {
             // deposit: fp32 piece (pixel t, filters 4*c16 .. +3) at staging[t*SPR + (c16 ^ (t & 15))]
 #pragma unroll
@@ -416,29 +659,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             }
             continue;
         }
-        const TileCoord tc = decode_tile<BN>(tile, g);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
-            if (p < s.P && q < s.Q) {
-                TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        const int col = tc.k0 + (wave_n * NI + ni) * 32 + 8 * gq + 4 * fk;
-                        if (vec_ok && col + 3 < s.K) {
-                            store4<TO>(yrow + col, acc[mi][ni][4 * gq], acc[mi][ni][4 * gq + 1], acc[mi][ni][4 * gq + 2],
-                                       acc[mi][ni][4 * gq + 3]);
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (col + e < s.K) yrow[col + e] = to_out<TO>(acc[mi][ni][4 * gq + e]);
-                        }
-                    }
-                }
-            }
-        }
+        store_tile(tile, acc);
     }
     if (SS > 0) __syncthreads();                // hands the last tile to the loader waves
 }
@@ -447,10 +668,15 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 
 struct PatchCfg {
     const char* name;
-    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw;
+    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw, ks, pf;
     int bm() const { return waves_m * mi * 32; }
     int bn() const { return waves_n * ni * 32; }
-    int waves() const { return waves_m * waves_n + nld + nsw; }   // compute + loader + store waves
+    int waves() const { return waves_m * waves_n * ks + nld + nsw; }   // compute + loader + store waves
+    // LDS after the patches, the filter ring and the sinks: output staging (ss > 0) or the K-split exchange area
+    long tail_bytes() const {
+        if (ss > 0) return (long)bm() * bn() * 4;
+        return ks > 1 ? (long)waves_m * waves_n * ks * (ks - 1) * 4096 : 0;
+    }
 };
 
 constexpr int kLdsLimit = 160 * 1024;
@@ -482,7 +708,7 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
         const int per_pass = rpb * c.nld;
         const int a_blocks = (int)((npix + per_pass - 1) / per_pass);
         const long patch_bytes = (long)a_blocks * c.nld * 1024;
-        const long staging = c.ss > 0 ? (long)BM * c.bn() * 4 : 0;
+        const long staging = c.tail_bytes();
         const long lds = 2 * patch_bytes + (long)c.stb * c.bn() * c.cb * 2 + c.nld * 1024 + staging;
         if (lds > kLdsLimit) continue;
         // the next phase's patch must fit into the loads of the steps that may carry it
@@ -504,12 +730,13 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
     return found;
 }
 
-template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW>
+template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
+          int KS, int PF>
 hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     PatchGeom g;
     if (!plan_geometry(s, c, &g)) return hipErrorInvalidConfiguration;
-    const int lds_bytes = 2 * g.patch_bytes + STB * c.bn() * CB * 2 + NLD * 1024 + (SS > 0 ? c.bm() * c.bn() * 4 : 0);
-    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW>;
+    const int lds_bytes = 2 * g.patch_bytes + STB * c.bn() * CB * 2 + NLD * 1024 + (int)c.tail_bytes();
+    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW, KS, PF>;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
@@ -533,28 +760,46 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
     return hipGetLastError();
 }
 
-//   name                                  CB  WM WN MI NI STB LA NLD SS NSW
-// (compute + loader [+ store] waves; SS > 0: output staged in LDS and drained by NSW store waves)
-#define ICONV_PATCH_VARIANTS(X)                                                \
-    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0)           \
-    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0)           \
-    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0)          \
-    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0)          \
-    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4, 0, 0)          \
-    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0)           \
-    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4, 0, 0)           \
-    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0)            \
-    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0)           \
-    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4, 0, 0)          \
-    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0)        \
-    X(11, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2)        \
-    X(12, "p256x64_c64_w32x64_s3_8+4+2", 64, 8, 1, 1, 2, 3, 2, 4, 4, 2)        \
-    X(13, "p256x64_c64_w64x64_s3_4+4+2", 64, 4, 1, 2, 2, 3, 2, 4, 4, 2)        \
-    X(14, "p64x64_c64_w32x32_s3_4+4+2", 64, 2, 2, 1, 1, 3, 1, 4, 1, 2)         \
-    X(15, "p128x128_c64_w64x64_s3_4+4+2", 64, 2, 2, 2, 2, 3, 2, 4, 2, 2)       \
-    X(16, "p64x128_c64_w32x64_s3_4+4+2", 64, 2, 2, 1, 2, 3, 1, 4, 1, 2)
+//   name                                  CB  WM WN MI NI STB LA NLD SS NSW KS PF
+// (compute + loader [+ store] waves; SS > 0: output staged in LDS and drained by NSW store waves;
+//  KS > 1: KS waves per tile position share a fragment block and split the K slices of every step;
+//  PF: operands of the next group of K slices are read before the current group's MFMAs)
+#define ICONV_PATCH_VARIANTS(X)                                                      \
+    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0, 1, 0)           \
+    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 1, 0)           \
+    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0, 1, 0)          \
+    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1, 0)          \
+    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4, 0, 0, 1, 0)          \
+    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 1, 0)           \
+    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4, 0, 0, 1, 0)           \
+    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 1, 0)            \
+    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1, 0)           \
+    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4, 0, 0, 1, 0)          \
+    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 1, 0)        \
+    X(11, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 1, 0)        \
+    X(12, "p256x64_c64_w32x64_s3_8+4+2", 64, 8, 1, 1, 2, 3, 2, 4, 4, 2, 1, 0)        \
+    X(13, "p256x64_c64_w64x64_s3_4+4+2", 64, 4, 1, 2, 2, 3, 2, 4, 4, 2, 1, 0)        \
+    X(14, "p64x64_c64_w32x32_s3_4+4+2", 64, 2, 2, 1, 1, 3, 1, 4, 1, 2, 1, 0)         \
+    X(15, "p128x128_c64_w64x64_s3_4+4+2", 64, 2, 2, 2, 2, 3, 2, 4, 2, 2, 1, 0)       \
+    X(16, "p64x128_c64_w32x64_s3_4+4+2", 64, 2, 2, 1, 2, 3, 1, 4, 1, 2, 1, 0)        \
+    X(17, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1, 1)      \
+    X(18, "p64x128_c64_w64x128k4_s4_4+4_pf", 64, 1, 1, 2, 4, 4, 1, 4, 0, 0, 4, 1)    \
+    X(19, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1, 1)       \
+    X(20, "p256x128_c64_w128x64_s3_4+4_pf", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 1, 1)     \
+    X(21, "p256x128_c32_w64x64_s5_8+4_pf", 32, 4, 2, 2, 2, 5, 1, 4, 0, 0, 1, 1)      \
+    X(22, "p128x128_c64_w64x64k2_s3_8+4_pf", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0, 2, 1)    \
+    X(23, "p256x64_c64_w64x64_s3_4+4_pf", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0, 1, 1)       \
+    X(24, "p64x128_c64_w32x64_s8_4+4", 64, 2, 2, 1, 2, 8, 2, 4, 0, 0, 1, 0)          \
+    X(25, "p64x128_c64_w32x64_s6_4+4", 64, 2, 2, 1, 2, 6, 1, 4, 0, 0, 1, 0)          \
+    X(26, "p64x128_c64_w32x64_s8_4+4_pf", 64, 2, 2, 1, 2, 8, 2, 4, 0, 0, 1, 1)       \
+    X(27, "p64x128_c64_w32x64_s3_4+8", 64, 2, 2, 1, 2, 3, 1, 8, 0, 0, 1, 0)          \
+    X(28, "p256x128_c64_w64x64_s3_8+8", 64, 4, 2, 2, 2, 3, 1, 8, 0, 0, 1, 0)         \
+    X(29, "p64x128_c64_w32x64_s4_4+8", 64, 2, 2, 1, 2, 4, 1, 8, 0, 0, 1, 0)          \
+    X(30, "p64x128_c128_w32x64_s3_4+4_pf", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1, 1)     \
+    X(31, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1, 0)        \
+    X(32, "p64x128_c128_w64x128k4_s3_4+4_pf", 128, 1, 1, 2, 4, 3, 1, 4, 0, 0, 4, 1)
 
-#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw},
+#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf},
 const PatchCfg kPatchCfgs[] = {ICONV_PATCH_VARIANTS(X_CFG)};
 #undef X_CFG
 constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
@@ -562,8 +807,8 @@ constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
 template <typename T, typename TO>
 hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     switch (v) {
-#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw) \
-    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw>(kPatchCfgs[i], x, w, y, s, st);
+#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf) \
+    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf>(kPatchCfgs[i], x, w, y, s, st);
         ICONV_PATCH_VARIANTS(X_CASE)
 #undef X_CASE
         default: return hipErrorInvalidValue;

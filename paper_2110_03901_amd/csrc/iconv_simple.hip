@@ -72,21 +72,36 @@ __global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src
 }
 
 // Register-only MFMA loop: eight independent accumulator tiles per wave, operands never reloaded.
+// RANDOM = false: one small-integer operand pair for all MFMAs (few bits toggle between
+// instructions); RANDOM = true: four operand pairs of pseudo-random values in +-[0.5, 1), a
+// different pair on consecutive MFMAs, which is what real data does to the multiplier inputs.
+template <bool RANDOM>
 __global__ void __launch_bounds__(256) mfma_probe_kernel(float* __restrict__ out, int iters) {
     floatx16 acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-    bf16x8 a, b;
+    bf16x8 a[4], b[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        a[j] = (bf16_t)(float)((threadIdx.x + j) & 7);
-        b[j] = (bf16_t)(float)(j + 1);
-    }
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (RANDOM) {
+                uint32_t h = (uint32_t)(blockIdx.x * 256 + threadIdx.x) * 2654435761u + (uint32_t)(r * 8 + j) * 40503u;
+                h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+                const uint16_t ua = (uint16_t)((h & 0x807fu) | 0x3f00u), ub = (uint16_t)(((h >> 16) & 0x807fu) | 0x3f00u);
+                a[r][j] = __builtin_bit_cast(bf16_t, ua);
+                b[r][j] = __builtin_bit_cast(bf16_t, ub);
+            } else {
+                a[r][j] = (bf16_t)(float)((threadIdx.x + j) & 7);
+                b[r][j] = (bf16_t)(float)(j + 1);
+            }
+        }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[RANDOM ? (i & 3) : 0], b[RANDOM ? ((i >> 1) & 3) : 0], acc[i], 0, 0, 0);
     }
     float sum = 0.f;
 #pragma unroll
@@ -159,8 +174,11 @@ hipError_t launch_im2col(const void* x, void* low, const ConvShape& s, int elt_b
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_probe(void* out, int iters, hipStream_t st) {
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(kMfmaProbeGroups), dim3(256), 0, st, (float*)out, iters);
+hipError_t launch_mfma_probe(void* out, int iters, bool random_operands, hipStream_t st) {
+    if (random_operands)
+        hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3(kMfmaProbeGroups), dim3(256), 0, st, (float*)out, iters);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(kMfmaProbeGroups), dim3(256), 0, st, (float*)out, iters);
     return hipGetLastError();
 }
 

@@ -350,5 +350,8 @@ def test_probes_run_and_are_exact(B):
     total_per_wave = 8 * (A @ Bm).sum()            # eight accumulator tiles per wave
     got = out.double().view(-1, 64).sum(dim=1).cpu().numpy()
     assert np.array_equal(got, np.full_like(got, total_per_wave))
+    B.iconv_probe_mfma(out, out.numel() * 4, 4, True)        # pseudo-random operands of magnitude < 1
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and float(out.abs().max()) < 8 * 16 * 4 * 16 * 4
     with pytest.raises(B.IconvError):
         B.iconv_probe_mfma(out, 16, 1)
