@@ -256,13 +256,7 @@ hipError_t launch_dma(const void* x, const void* w, void* y, const ConvShape& s,
     X(4, "d256x256x32_w128x64_s3", (launch_dma<T, TO, 256, 256, 32, 128, 64, 3>)) \
     X(5, "d64x64x64_w32x32_s4", (launch_dma<T, TO, 64, 64, 64, 32, 32, 4>))       \
     X(6, "d128x128x64_w64x32_s3", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3>))   \
-    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))     \
-    X(8, "d128x128x64_w64x64_s5", (launch_dma<T, TO, 128, 128, 64, 64, 64, 5>))   \
-    X(9, "d128x128x64_w64x64_s4", (launch_dma<T, TO, 128, 128, 64, 64, 64, 4>))   \
-    X(10, "d128x128x32_w64x64_s8", (launch_dma<T, TO, 128, 128, 32, 64, 64, 8>))  \
-    X(11, "d256x256x32_w128x64_s5", (launch_dma<T, TO, 256, 256, 32, 128, 64, 5>)) \
-    X(12, "d128x64x64_w64x32_s6", (launch_dma<T, TO, 128, 64, 64, 64, 32, 6>))    \
-    X(13, "d256x128x32_w64x64_s6", (launch_dma<T, TO, 256, 128, 32, 64, 64, 6>))
+    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))
 
 #define X_NAME(i, name, fn) name,
 const char* const kVariantNames[] = {ICONV_VARIANTS(X_NAME)};
@@ -297,9 +291,11 @@ int choose_variant(const ConvShape& s) {
     if (s.R * s.S > 1 && s.stride == 1) {
         int v;
         if (s.K <= 64) v = P0 + 5;                    // p256x64, eight compute waves of 32x64
-        else if (tiles_256x128 >= 200) v = P0 + 3;    // p256x128
-        else v = P0 + 8;                              // p64x128: many small tiles
+        else if (tiles_256x128 >= 200) v = P0 + 17;   // p256x128, operands prefetched one group of K slices ahead
+        else if (s.C % 128 == 0) v = P0 + 20;         // p64x128 (many small tiles), 128-channel chunks: half the steps
+        else v = P0 + 19;                             // p64x128, prefetching
         if (patch_supported(s, v - P0)) return v;
+        if (v != P0 + 8 && s.K > 64 && patch_supported(s, 8)) return P0 + 8;
     }
     if (s.R * s.S == 1) {
         const long tiles_256x256 = (long)((s.M + 255) / 256) * ((s.K + 255) / 256);

@@ -83,10 +83,10 @@ template <int BN> __device__ __forceinline__ TileCoord decode_tile(int t, const 
 template <int V> struct IntTag { static constexpr int value = V; };
 
 template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
-          int KS, int PF>
-__global__ void __launch_bounds__((WAVES_M * WAVES_N * KS + NLD + NSW) * 64)
+          int PF>
+__global__ void __launch_bounds__((WAVES_M * WAVES_N + NLD + NSW) * 64)
 ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const PatchGeom g) {
-    constexpr int WAVES_C = WAVES_M * WAVES_N * KS;  // compute waves
+    constexpr int WAVES_C = WAVES_M * WAVES_N;  // compute waves
     constexpr int CPR = CB / 8;                 // 16-byte chunks per pixel (or filter row) and channel chunk
     constexpr int RPB = 64 / CPR;               // pixels (filter rows) one wave-wide load covers
     constexpr int PPW = 16 / CPR;               // pixels per 256-byte LDS window
@@ -102,15 +102,10 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     constexpr int ST_ROWS = 64 / SPR;           // staging rows one wave-wide store covers
     constexpr int ST_IT = SS > 0 ? BM / ST_ROWS / (NSW > 0 ? NSW : 1) : 0;   // wave-wide stores per store wave per tile
     static_assert((STB - 2) * B_IT + (STB - 1) * LA < 64, "too many loads in flight for vmcnt");
-    static_assert(KS >= 1 && KI % KS == 0 && (MI * NI) % KS == 0, "K slices and fragments must divide over the K-split waves");
     static_assert(PF == 0 || (STB >= 3 && SS == 0), "the prefetching pipeline needs three filter stages and stores its own output");
-    static_assert(KS == 1 || PF == 1, "K-split waves are built on the prefetching pipeline only");
     // Steady-state loads that may stay in flight when a step's barrier is reached.  Without
     // prefetch the step's own filter tile must have landed; with prefetch (PF) the NEXT step's must.
     constexpr int WAIT_STEP = PF ? (STB - 3) * B_IT + (STB - 2) * LA : (STB - 2) * B_IT + (STB - 1) * LA;
-    // K-split reduction: per round every wave hands KS-1 fragments (4 KiB each) to their owners
-    constexpr int RED_ROUNDS = KS > 1 ? (MI * NI) / KS : 0;
-    constexpr int RED_BARRIERS = KS > 1 ? 2 * RED_ROUNDS - 1 : 0;
     static_assert((SS == 0 && NSW == 0) || (SS > 0 && NSW > 0 && BM % (ST_ROWS * NSW) == 0 && SPR <= 64),
                   "staging rows must divide over the store waves");
     typedef typename Elem<T>::frag frag_t;
@@ -130,7 +125,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     const int phases = (t_end - t_begin) * chunks;           // (tile, channel chunk) pairs of this workgroup
     const int steps = phases * RS;
     const uint32_t bstage_off = 2u * (uint32_t)g.patch_bytes;   // byte offset of the filter ring
-    const uint32_t staging_off = bstage_off + STB * BSTAGE_BYTES + NLD * 1024;   // byte offset of the staging buffer (SS > 0) or of the K-split exchange area (KS > 1)
+    const uint32_t staging_off = bstage_off + STB * BSTAGE_BYTES + NLD * 1024;   // byte offset of the staging buffer
     const int steps_per_tile = chunks * RS;
     // which bits of the window number the patch swizzle XORs into the slot number (see above)
     const int wmask = (s.stride & 1) ? (CPR - 1) : 15;
@@ -171,8 +166,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 a_n = tc.n;
                 a_hb = tc.p0 * s.stride - s.pad;
                 a_wb = tc.q0 * s.stride - s.pad;
-                const int ck = phase % chunks + (t_begin + phase / chunks) % chunks;   // rotated chunk order, see filter_load
-                a_c0 = (ck >= chunks ? ck - chunks : ck) * CB;
+                a_c0 = (phase % chunks) * CB;
                 a_buf = phase & 1;
             }
         };
@@ -209,14 +203,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             }
         };
         filter_tile();
-        // Tap (lr_, ls_) of channel chunk lc0 is loaded next.  Tile t walks its channel chunks in the
-        // rotated order (t % chunks), (t % chunks) + 1, ..., wrapping around (the order of summation is
-        // free, section 3.2): workgroups that run side by side then read different chunks at any
-        // moment.  With one common order they would all fetch the same 16-byte column range of every
-        // filter row at once, addresses that differ by multiples of the row length and land on few
-        // memory channels.
-        int lr_ = 0, ls_ = 0, lck = 0, lrot = t_begin % chunks;
-        int lc0 = lrot * CB;
+        int lr_ = 0, ls_ = 0, lc0 = 0;          // tap (lr_, ls_) of channel chunk lc0 to load next
         auto filter_load = [&](int stage, bool live) {
             const uint32_t delta = (uint32_t)((lr_ * s.S + ls_) * s.C + lc0) * 2u;     // tap and chunk: uniform
             if (!live) {
@@ -243,13 +230,11 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 ls_ = 0;
                 if (++lr_ == s.R) {
                     lr_ = 0;
-                    if (++lck == chunks) {      // next tile
-                        lck = 0;
+                    lc0 += CB;
+                    if (lc0 >= s.C) {           // next tile
+                        lc0 = 0;
                         if (++b_tile < t_end) filter_tile();
-                        lrot = b_tile % chunks;
                     }
-                    const int ck = lck + lrot;
-                    lc0 = (ck >= chunks ? ck - chunks : ck) * CB;
                 }
             }
         };
@@ -271,7 +256,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             wait_vmcnt<(STB - 2) * B_IT + (STB - 1) * LA>();
             __syncthreads();
         }
-        int fill = STB - 1, step = 0, tile_step = 0;
+        int fill = STB - 1, step = 0;
         for (int phase = 0; phase < phases; ++phase) {
             patch_begin(phase + 1);
             for (int t = 0; t < RS; ++t, ++step) {
@@ -288,12 +273,6 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 #pragma unroll
                 for (int l = 0; l < LA; ++l) patch_load(t <= RS - STB);
                 fill = fill + 1 == STB ? 0 : fill + 1;
-                if (KS > 1 && ++tile_step == steps_per_tile) {
-                    // the compute waves' exchange of partial sums at the end of a tile
-                    tile_step = 0;
-#pragma unroll
-                    for (int b = 0; b < RED_BARRIERS; ++b) __syncthreads();
-                }
             }
         }
         wait_vmcnt<0>();
@@ -350,8 +329,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     }
 
     // =============================== compute waves ==============================================
-    const int ks = wave % KS, pos = wave / KS;  // K-split index and tile position of this wave
-    const int wave_m = pos / WAVES_N, wave_n = pos % WAVES_N;
+    const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.TH * g.TW;
     int a_base[MI];                             // patch pixel of each A-fragment row at tap (0, 0)
@@ -381,6 +359,33 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     // (16-bit) piece of the pixel's y row.  The stores are not waited for.
     auto store_tile = [&](int tile, floatx16 (&acc)[MI][NI]) __attribute__((always_inline)) {
         const TileCoord tc = decode_tile<BN>(tile, g);
+        // The workgroup's LAST tile has nothing left to overlap its stores with, and the loader waves
+        // end after its last step: once every compute wave is here LDS is free, and the fragments go
+        // through wave-private staging areas so that each store covers whole 128-byte lines.  (A
+        // barrier counts live waves only, so the ended loader waves do not take part.)
+        if (SS == 0 && tile == t_end - 1 && vec_ok && (long long)g.TH * s.Q * s.K * (long long)sizeof(TO) < 0x7fffffffLL) {
+            __syncthreads();
+            char* stg = reinterpret_cast<char*>(lds) + wave * kFragStageBytes;
+            const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
+            const size_t rem = ((size_t)s.M * s.K - org) * sizeof(TO);
+            const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0x7fffffffull ? 0x7fffffffu : (uint32_t)rem,
+                                                                   kRsrcFlags);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int col0 = tc.k0 + (wave_n * NI + ni) * 32;
+                    const bool pieces_ok = col0 + 4 * (lane & 7) + 3 < s.K;
+                    store_frag_staged<TO>(stg, acc[mi][ni], lane, y_rsrc, pieces_ok, [&](int i) {
+                        const int t = (wave_m * MI + mi) * 32 + i;
+                        const int th = (int)(((float)t + 0.5f) * g.inv_tw);
+                        const int tw = t - th * g.TW;
+                        const bool ok = (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q);
+                        return ok ? (uint32_t)((th * s.Q + tw) * s.K + col0) * (uint32_t)sizeof(TO) : 0x80000000u;
+                    });
+                }
+            return;
+        }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
@@ -388,7 +393,6 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
-                    if (KS > 1 && (mi * NI + ni) % KS != ks) continue;      // another wave's fragment
 #pragma unroll
                     for (int gq = 0; gq < 4; ++gq) {
                         const int col = tc.k0 + (wave_n * NI + ni) * 32 + 8 * gq + 4 * fk;
@@ -407,24 +411,12 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     };
 
     if constexpr (PF != 0) {
-        // ---- prefetching pipeline.  The wave's K slices of a step (slices ks, ks + KS, ... of the
-        // chunk) form KG groups of KPG slices.  The operands of group g + 1 are read from LDS
+        // ---- prefetching pipeline.  The K slices of a step form KG groups of KPG slices.  The operands of group g + 1 are read from LDS
         // before the MFMAs of group g are issued, across step boundaries too: the first group of
         // step i + 1 is read during step i.  The matrix pipe therefore never waits for an LDS read
         // after a barrier; in return the loaders keep one more filter stage complete.
-        constexpr int KIW = KI / KS;                // K slices of this wave per step
-        constexpr int KPG = KIW >= 4 ? 2 : 1;       // slices per group
-        constexpr int KG = KIW / KPG;               // groups per step
-        int kx[KIW];                                // chunk-index XOR term of each of the wave's slices
-#pragma unroll
-        for (int j = 0; j < KIW; ++j) kx[j] = (ks + KS * j) * 2;
-        int b_own[NI][KIW];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            const int row = (wave_n * NI + ni) * 32 + frow;
-#pragma unroll
-            for (int j = 0; j < KIW; ++j) b_own[ni][j] = row * CPR + swz<CPR>(row, kx[j] + fk);
-        }
+        constexpr int KPG = KI >= 4 ? 2 : 1;        // slices per group
+        constexpr int KG = KI / KPG;                // groups per step
         // read cursor: the step whose operands are fetched next
         int r_stage = 0, r_phase = 0, r_tr = 0, r_ts = 0;
         int a_win[MI], a_sx[MI];
@@ -458,9 +450,9 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 constexpr int j0 = gk * KPG;
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    af[buf][k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ kx[j0 + k2])]);
+                    af[buf][k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ ((j0 + k2) * 2))]);
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) bfr[buf][k2][ni] = __builtin_bit_cast(frag_t, Bt[b_own[ni][j0 + k2]]);
+                for (int ni = 0; ni < NI; ++ni) bfr[buf][k2][ni] = __builtin_bit_cast(frag_t, Bt[b_idx[ni][j0 + k2]]);
             }
         };
 
@@ -473,52 +465,6 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
         };
-        // End of a tile.  With K-split waves the KS partial sums of every fragment meet at the
-        // fragment's owner (fragment f belongs to wave f % KS of its position) through an exchange
-        // area in LDS: per round each wave deposits the KS-1 fragments of that round it does not own
-        // (lane-linear 16-byte pieces), one barrier, the owner adds them in a fixed order.
-        auto finish_tile = [&](int tile) __attribute__((always_inline)) {
-            if constexpr (KS > 1) {
-                u32x4* red = lds + (staging_off >> 4) + pos * (KS * (KS - 1) * 256);
-#pragma unroll
-                for (int rd = 0; rd < RED_ROUNDS; ++rd) {
-#pragma unroll
-                    for (int fl = 0; fl < KS; ++fl) {
-                        const int f = rd * KS + fl;
-                        if (ks != fl) {
-                            const int src = ks > fl ? ks - 1 : ks;
-                            u32x4* dst = red + (fl * (KS - 1) + src) * 256 + lane;
-#pragma unroll
-                            for (int v4 = 0; v4 < 4; ++v4) {
-                                floatx4 v = {acc[f / NI][f % NI][4 * v4], acc[f / NI][f % NI][4 * v4 + 1],
-                                             acc[f / NI][f % NI][4 * v4 + 2], acc[f / NI][f % NI][4 * v4 + 3]};
-                                dst[v4 * 64] = __builtin_bit_cast(u32x4, v);
-                            }
-                        }
-                    }
-                    __syncthreads();
-#pragma unroll
-                    for (int fl = 0; fl < KS; ++fl) {
-                        const int f = rd * KS + fl;
-                        if (ks == fl) {
-#pragma unroll
-                            for (int src = 0; src < KS - 1; ++src) {
-                                const u32x4* from = red + (fl * (KS - 1) + src) * 256 + lane;
-#pragma unroll
-                                for (int v4 = 0; v4 < 4; ++v4) {
-                                    const floatx4 v = __builtin_bit_cast(floatx4, from[v4 * 64]);
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) acc[f / NI][f % NI][4 * v4 + e] += v[e];
-                                }
-                            }
-                        }
-                    }
-                    if (rd != RED_ROUNDS - 1) __syncthreads();
-                }
-            }
-            store_tile(tile, acc);
-        };
-
         int tile = t_begin, tile_step = 0;
         auto one_step = [&](auto PAR) __attribute__((always_inline)) {             // PAR: register buffer that holds this step's first group
             constexpr int par = decltype(PAR)::value;
@@ -560,7 +506,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 if constexpr (KG > 3) body(IntTag<3>{});
             }
             if (++tile_step == steps_per_tile) {
-                finish_tile(tile);
+                store_tile(tile, acc);
                 tile_step = 0;
                 ++tile;
                 clear_acc();
@@ -668,15 +614,12 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 
 struct PatchCfg {
     const char* name;
-    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw, ks, pf;
+    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw, pf;
     int bm() const { return waves_m * mi * 32; }
     int bn() const { return waves_n * ni * 32; }
-    int waves() const { return waves_m * waves_n * ks + nld + nsw; }   // compute + loader + store waves
-    // LDS after the patches, the filter ring and the sinks: output staging (ss > 0) or the K-split exchange area
-    long tail_bytes() const {
-        if (ss > 0) return (long)bm() * bn() * 4;
-        return ks > 1 ? (long)waves_m * waves_n * ks * (ks - 1) * 4096 : 0;
-    }
+    int waves() const { return waves_m * waves_n + nld + nsw; }   // compute + loader + store waves
+    // LDS after the patches, the filter ring and the sinks: output staging for the store waves
+    long tail_bytes() const { return ss > 0 ? (long)bm() * bn() * 4 : 0; }
 };
 
 constexpr int kLdsLimit = 160 * 1024;
@@ -731,12 +674,12 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
 }
 
 template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
-          int KS, int PF>
+          int PF>
 hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     PatchGeom g;
     if (!plan_geometry(s, c, &g)) return hipErrorInvalidConfiguration;
     const int lds_bytes = 2 * g.patch_bytes + STB * c.bn() * CB * 2 + NLD * 1024 + (int)c.tail_bytes();
-    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW, KS, PF>;
+    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW, PF>;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
@@ -760,46 +703,34 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
     return hipGetLastError();
 }
 
-//   name                                  CB  WM WN MI NI STB LA NLD SS NSW KS PF
+//   name                                  CB  WM WN MI NI STB LA NLD SS NSW PF
 // (compute + loader [+ store] waves; SS > 0: output staged in LDS and drained by NSW store waves;
-//  KS > 1: KS waves per tile position share a fragment block and split the K slices of every step;
 //  PF: operands of the next group of K slices are read before the current group's MFMAs)
-#define ICONV_PATCH_VARIANTS(X)                                                      \
-    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0, 1, 0)           \
-    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 1, 0)           \
-    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0, 1, 0)          \
-    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1, 0)          \
-    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4, 0, 0, 1, 0)          \
-    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 1, 0)           \
-    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4, 0, 0, 1, 0)           \
-    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 1, 0)            \
-    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1, 0)           \
-    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4, 0, 0, 1, 0)          \
-    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 1, 0)        \
-    X(11, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 1, 0)        \
-    X(12, "p256x64_c64_w32x64_s3_8+4+2", 64, 8, 1, 1, 2, 3, 2, 4, 4, 2, 1, 0)        \
-    X(13, "p256x64_c64_w64x64_s3_4+4+2", 64, 4, 1, 2, 2, 3, 2, 4, 4, 2, 1, 0)        \
-    X(14, "p64x64_c64_w32x32_s3_4+4+2", 64, 2, 2, 1, 1, 3, 1, 4, 1, 2, 1, 0)         \
-    X(15, "p128x128_c64_w64x64_s3_4+4+2", 64, 2, 2, 2, 2, 3, 2, 4, 2, 2, 1, 0)       \
-    X(16, "p64x128_c64_w32x64_s3_4+4+2", 64, 2, 2, 1, 2, 3, 1, 4, 1, 2, 1, 0)        \
-    X(17, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1, 1)      \
-    X(18, "p64x128_c64_w64x128k4_s4_4+4_pf", 64, 1, 1, 2, 4, 4, 1, 4, 0, 0, 4, 1)    \
-    X(19, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1, 1)       \
-    X(20, "p256x128_c64_w128x64_s3_4+4_pf", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 1, 1)     \
-    X(21, "p256x128_c32_w64x64_s5_8+4_pf", 32, 4, 2, 2, 2, 5, 1, 4, 0, 0, 1, 1)      \
-    X(22, "p128x128_c64_w64x64k2_s3_8+4_pf", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0, 2, 1)    \
-    X(23, "p256x64_c64_w64x64_s3_4+4_pf", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0, 1, 1)       \
-    X(24, "p64x128_c64_w32x64_s8_4+4", 64, 2, 2, 1, 2, 8, 2, 4, 0, 0, 1, 0)          \
-    X(25, "p64x128_c64_w32x64_s6_4+4", 64, 2, 2, 1, 2, 6, 1, 4, 0, 0, 1, 0)          \
-    X(26, "p64x128_c64_w32x64_s8_4+4_pf", 64, 2, 2, 1, 2, 8, 2, 4, 0, 0, 1, 1)       \
-    X(27, "p64x128_c64_w32x64_s3_4+8", 64, 2, 2, 1, 2, 3, 1, 8, 0, 0, 1, 0)          \
-    X(28, "p256x128_c64_w64x64_s3_8+8", 64, 4, 2, 2, 2, 3, 1, 8, 0, 0, 1, 0)         \
-    X(29, "p64x128_c64_w32x64_s4_4+8", 64, 2, 2, 1, 2, 4, 1, 8, 0, 0, 1, 0)          \
-    X(30, "p64x128_c128_w32x64_s3_4+4_pf", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1, 1)     \
-    X(31, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1, 0)        \
-    X(32, "p64x128_c128_w64x128k4_s3_4+4_pf", 128, 1, 1, 2, 4, 3, 1, 4, 0, 0, 4, 1)
+#define ICONV_PATCH_VARIANTS(X)                                                   \
+    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0, 0)           \
+    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 0)           \
+    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0, 0)          \
+    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 0)          \
+    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4, 0, 0, 0)          \
+    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 0)           \
+    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4, 0, 0, 0)           \
+    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 0)            \
+    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)           \
+    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4, 0, 0, 0)          \
+    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 0)        \
+    X(11, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 0)        \
+    X(12, "p256x64_c64_w32x64_s3_8+4+2", 64, 8, 1, 1, 2, 3, 2, 4, 4, 2, 0)        \
+    X(13, "p256x64_c64_w64x64_s3_4+4+2", 64, 4, 1, 2, 2, 3, 2, 4, 4, 2, 0)        \
+    X(14, "p64x64_c64_w32x32_s3_4+4+2", 64, 2, 2, 1, 1, 3, 1, 4, 1, 2, 0)         \
+    X(15, "p128x128_c64_w64x64_s3_4+4+2", 64, 2, 2, 2, 2, 3, 2, 4, 2, 2, 0)       \
+    X(16, "p64x128_c64_w32x64_s3_4+4+2", 64, 2, 2, 1, 2, 3, 1, 4, 1, 2, 0)        \
+    X(17, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1)      \
+    X(18, "p256x128_c64_w128x64_s3_4+4_pf", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 1)     \
+    X(19, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1)       \
+    X(20, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)        \
+    X(21, "p64x128_c128_w32x64_s3_4+4_pf", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1)
 
-#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf},
+#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf},
 const PatchCfg kPatchCfgs[] = {ICONV_PATCH_VARIANTS(X_CFG)};
 #undef X_CFG
 constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
@@ -807,8 +738,8 @@ constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
 template <typename T, typename TO>
 hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     switch (v) {
-#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf) \
-    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, ks, pf>(kPatchCfgs[i], x, w, y, s, st);
+#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf) \
+    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf>(kPatchCfgs[i], x, w, y, s, st);
         ICONV_PATCH_VARIANTS(X_CASE)
 #undef X_CASE
         default: return hipErrorInvalidValue;
