@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0       # HBM3E, MI355X datasheet
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, scaled by the same counters' reading for the copy probe (see profiles/): layer -> bytes
-MEASURED_TRAFFIC_BYTES = {"cfg2": 39_350_000, "cfg3a": 41_080_000, "cfg3b": 67_470_000, "cfg4": 59_940_000,
-                          "cfg5a": 242_590_000, "cfg5b": 47_500_000}   # profiles/bench_all_layers_pmc.txt
+MEASURED_TRAFFIC_BYTES = {"cfg2": 39_350_000, "cfg3a": 41_090_000, "cfg3b": 66_720_000, "cfg4": 59_940_000,
+                          "cfg5a": 242_640_000, "cfg5b": 47_560_000}   # profiles/bench_all_layers_pmc.txt
 
 
 def main():
