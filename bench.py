@@ -184,6 +184,18 @@ def main():
             del xd, wd, y
             torch.cuda.empty_cache()
             return t
+        def quick_channel_last(Li):
+            """The channel-last comparison kernel on the same layer (NCHW input, KCRS filters)."""
+            c = B.DTYPE_CODES[Li.dtype]
+            x, w = workloads.make_inputs(Li)
+            xd = B.to_device(x, c).permute(0, 3, 1, 2).contiguous()
+            wd = B.to_device(w, c).permute(0, 3, 1, 2).contiguous()
+            y = B.empty_output(Li.N, Li.P, Li.Q, Li.K, c)
+            sa = Li.shape_args()
+            t = time_steps(lambda: B.iconv_fwd_channel_last(xd, wd, y, *sa, c), 50, 10)
+            del xd, wd, y
+            torch.cuda.empty_cache()
+            return t
         study = {"stride_dilation": {}, "batch": {}, "output_type": {}}
         # (1) stride / dilation sensitivity: the convolution against the plain GEMM of the same M x K_gemm x K
         # shape (a 1x1 convolution over a 1 x 1 x M image with K_gemm channels), as in the paper's stride figure
@@ -191,9 +203,12 @@ def main():
             t_conv = quick(Ls)
             Lg = workloads.ConvLayer("gemm_" + label, 1, 1, Ls.M, Ls.k_gemm, Ls.K, 1, 1, 1, 0, 1, Ls.dtype, Ls.seed_id + 1)
             t_gemm = quick(Lg)
+            t_cl = quick_channel_last(Ls)
             study["stride_dilation"][label] = {"M": Ls.M, "us": round(t_conv * 1e3, 2), "tflops": round(Ls.flops / t_conv / 1e9, 1),
                                                "gemm_only_us": round(t_gemm * 1e3, 2),
-                                               "conv_over_gemm_time": round(t_conv / t_gemm, 3)}
+                                               "conv_over_gemm_time": round(t_conv / t_gemm, 3),
+                                               "channel_last_us": round(t_cl * 1e3, 2),
+                                               "channel_last_over_gemm_time": round(t_cl / t_gemm, 3)}
         # (2) batch 8 and 64 for every benchmark layer
         for name, Li in workloads.LAYERS.items():
             if name == "cfg1":

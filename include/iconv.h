@@ -78,6 +78,18 @@ int iconv_fwd(const void *x_nhwc, const void *w_krsc, void *y_npqk,
 size_t iconv_workspace_bytes(int algo, int N, int H, int W, int C, int K, int R, int S,
                              int stride, int pad, int dilation, int dtype);
 
+/* Channel-last implicit im2col (sections 2.3 and 3.1): the conventional design the paper's
+ * channel-first method is compared with, built as a second in-run comparison for the stride
+ * study.  Same operation and result contract as iconv_fwd (y in NPQK, fully overwritten, fp32
+ * accumulation), but the lowered columns are ordered channel, tap row, tap column, so the
+ * tensors arrive in the layouts that order reads contiguously:
+ *   x_nchw[((n*C + c)*H + h)*W + w]     w_kcrs[((k*C + c)*R + r)*S + s]
+ * dtype: the 16-bit input codes only (ICONV_BF16_F32, ICONV_F16_F32, ICONV_BF16_BF16,
+ * ICONV_F16_F16); ICONV_F32_F32 returns ICONV_ERR_UNSUPPORTED.  No workspace; errors as iconv_fwd. */
+int iconv_fwd_channel_last(const void *x_nchw, const void *w_kcrs, void *y_npqk,
+                           int N, int H, int W, int C, int K, int R, int S,
+                           int stride, int pad, int dilation, int dtype, void *stream);
+
 /* Explicit im2col followed by a GEMM (section 2.2): the comparison the paper argues against.
  * Kernel 1 writes the lowered M x (R*S*C) matrix (columns in tap-row, tap-column, channel
  * order) into `workspace`; kernel 2 multiplies it with the filter matrix using the same MFMA

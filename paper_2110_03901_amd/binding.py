@@ -37,6 +37,8 @@ _lib.iconv_workspace_bytes.restype = _sz
 _lib.iconv_workspace_bytes.argtypes = [_i] * 12
 _lib.iconv_fwd_explicit.restype = _i
 _lib.iconv_fwd_explicit.argtypes = [_p, _p, _p, _p, _sz] + [_i] * 11 + [_p]
+_lib.iconv_fwd_channel_last.restype = _i
+_lib.iconv_fwd_channel_last.argtypes = [_p, _p, _p] + [_i] * 11 + [_p]
 _lib.iconv_im2col.restype = _i
 _lib.iconv_im2col.argtypes = [_p, _p, _sz] + [_i] * 10 + [_p]
 _lib.iconv_probe_copy.restype = _i
@@ -53,7 +55,7 @@ _lib.iconv_variant_name.argtypes = [_i]
 _lib.iconv_status_string.restype = ctypes.c_char_p
 _lib.iconv_status_string.argtypes = [_i]
 
-EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
+EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
            "iconv_probe_copy", "iconv_probe_mfma", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name",
            "iconv_status_string"]
 
@@ -100,6 +102,13 @@ def iconv_fwd_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, st
 
 def iconv_fwd(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream=None) -> None:
     rc = iconv_fwd_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream)
+    if rc != 0:
+        raise IconvError(rc)
+
+
+def iconv_fwd_channel_last(x_nchw, w_kcrs, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream=None) -> None:
+    rc = _lib.iconv_fwd_channel_last(_ptr(x_nchw), _ptr(w_kcrs), _ptr(y), N, H, W, C, K, R, S, stride, pad, dilation, dtype,
+                                     _stream(stream))
     if rc != 0:
         raise IconvError(rc)
 

@@ -85,6 +85,18 @@ int iconv_fwd(const void* x, const void* w, void* y, int N, int H, int W, int C,
     return run_conv(x, w, y, s, in_t, out_t, (hipStream_t)stream);
 }
 
+int iconv_fwd_channel_last(const void* x_nchw, const void* w_kcrs, void* y, int N, int H, int W, int C, int K, int R, int S,
+                           int stride, int pad, int dilation, int dtype, void* stream) {
+    if (!x_nchw || !w_kcrs || !y) return ICONV_ERR_NULL;
+    ConvShape s;
+    int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s);
+    if (rc != ICONV_OK) return rc;
+    int in_t, out_t;
+    if (!dtype_types(dtype, &in_t, &out_t) || in_t == IN_F32) return ICONV_ERR_UNSUPPORTED;
+    if (!aligned16(x_nchw) || !aligned16(w_kcrs) || !aligned16(y)) return ICONV_ERR_ALIGN;
+    return status_of(launch_channel_last(x_nchw, w_kcrs, y, s, in_t, out_t, (hipStream_t)stream));
+}
+
 size_t iconv_workspace_bytes(int algo, int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                              int dilation, int dtype) {
     ConvShape s;

@@ -84,6 +84,10 @@ bool stem_supported(const ConvShape& s);
 hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
                        hipStream_t stream);
 
+// Channel-last comparison kernel: NCHW input, KCRS filters, lowered columns ordered channel, tap row, tap column.
+hipError_t launch_channel_last(const void* x_nchw, const void* w_kcrs, void* y, const ConvShape& s, int in_t, int out_t,
+                               hipStream_t stream);
+
 hipError_t launch_im2col(const void* x, void* lowered, const ConvShape& s, int elt_bytes, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 constexpr int kMfmaProbeGroups = 1024;   // workgroups of the MFMA probe (four per compute unit)

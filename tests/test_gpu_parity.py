@@ -355,3 +355,52 @@ def test_probes_run_and_are_exact(B):
     assert bool(torch.isfinite(out).all()) and float(out.abs().max()) < 8 * 16 * 4 * 16 * 4
     with pytest.raises(B.IconvError):
         B.iconv_probe_mfma(out, 16, 1)
+
+
+CHANNEL_LAST = ["tile_tail", "c24_partial_chunk", "c72_k130", "stride2", "stride3_dil2", "dil2_pad2", "big_pad",
+                "one_by_one_s2", "p1_q1", "r5s3", "seven_by_seven", "single_pixel", "direct_c3", "stem_c4"]
+
+
+def run_channel_last(B, L, x, w, code):
+    """x (NHWC) and w (KRSC) reordered on the host into the layouts the channel-last entry point takes."""
+    xd = B.to_device(np.ascontiguousarray(x.transpose(0, 3, 1, 2)), code)      # NCHW
+    wd = B.to_device(np.ascontiguousarray(w.transpose(0, 3, 1, 2)), code)      # KCRS
+    y = B.empty_output(L.N, L.P, L.Q, L.K, code)
+    y.fill_(float("nan"))
+    B.iconv_fwd_channel_last(xd, wd, y, *L.shape_args(), code)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("case", [c for c in SMALL if c[0] in CHANNEL_LAST], ids=CHANNEL_LAST)
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_channel_last_comparison_kernel_small(B, case, dtype):
+    """The channel-last foil of the stride study computes the same convolution from NCHW / KCRS tensors."""
+    name, *dims = case
+    L = workloads.small_layer(name, *dims, dtype=dtype, seed_id=880 + len(name))
+    x, w = workloads.make_inputs(L)
+    ref = conv_ref(x, w, L.stride, L.pad, L.dilation)
+    err = rel_err(run_channel_last(B, L, x, w, code_of(L)), ref)
+    print(f"channel-last {L.name}: rel_err={err:.3e}", flush=True)
+    assert err <= TIGHT
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3a", "cfg3b"])
+def test_channel_last_comparison_kernel_benchmark_layers(B, name):
+    L = workloads.LAYERS[name]
+    x, w = workloads.make_inputs(L)
+    ref = conv_ref(x, w, L.stride, L.pad, L.dilation)
+    assert rel_err(run_channel_last(B, L, x, w, code_of(L)), ref) <= TIGHT
+    got16 = run_channel_last(B, L, x, w, code_of(L, out16=True))
+    assert np.abs(got16 - ref).max() <= np.abs(ref).max() * 2.0 ** -8 * 1.01       # bf16 output: one rounding of the largest value
+
+
+def test_channel_last_rejects_fp32_and_bad_arguments(B):
+    L = workloads.LAYERS["cfg1"]
+    t = torch.zeros(4096, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(B.IconvError) as e:
+        B.iconv_fwd_channel_last(t, t, t, *L.shape_args(), 0)
+    assert e.value.status == -3
+    with pytest.raises(B.IconvError) as e:
+        B.iconv_fwd_channel_last(t, t, None, *L.shape_args(), 1)
+    assert e.value.status == -1
