@@ -24,7 +24,9 @@ namespace {
 // later LDS read with a wait for *all* outstanding loads, and the kernel places its own
 // s_waitcnt vmcnt(n) so that the loads of the next ST-2 steps stay in flight during a step.
 // ---------------------------------------------------------------------------------------------
-template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int ST>
+template <int V> struct StepTag { static constexpr int value = V; };
+
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int ST, int PF>
 __global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64)
 igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s,
                  const int tiles_n, const int xcd_aware) {
@@ -129,6 +131,73 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
 
     const int frow = lane & 31, fk = lane >> 5;
 
+    if constexpr (PF != 0) {
+        // ---- prefetching pipeline: the operand fragments of step i + 1 are read from LDS between the
+        // MFMAs of step i (a wave issues in order, so only what sits between its MFMAs runs in
+        // their shadow), and the global loads of a later step follow the MFMAs.  The fragment
+        // registers act as one more stage: the ring holds ST stages in flight or landed, stage
+        // i + 1 must have landed at the barrier of step i, and the slot of stage i is refilled right
+        // after that barrier (every wave read it during step i - 1).
+        int a_idx[MI][KI], b_idx[NI][KI];       // fragment positions within a stage (16-byte units)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int row = wave_m * WM + mi * 32 + frow;
+#pragma unroll
+            for (int kk = 0; kk < KI; ++kk) a_idx[mi][kk] = row * CPR + swz<CPR>(row, kk * 2 + fk);
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int row = wave_n * WN + ni * 32 + frow;
+#pragma unroll
+            for (int kk = 0; kk < KI; ++kk) b_idx[ni][kk] = BM * CPR + row * CPR + swz<CPR>(row, kk * 2 + fk);
+        }
+        frag_t af[2][KI][MI], bfr[2][KI][NI];
+        auto read_stage = [&](int stage, auto BUF) __attribute__((always_inline)) {
+            constexpr int buf = decltype(BUF)::value;
+            const u32x4* S = lds + stage * STAGE_CHUNKS;
+#pragma unroll
+            for (int kk = 0; kk < KI; ++kk) {
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) af[buf][kk][mi] = __builtin_bit_cast(frag_t, S[a_idx[mi][kk]]);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) bfr[buf][kk][ni] = __builtin_bit_cast(frag_t, S[b_idx[ni][kk]]);
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < ST; ++j) issue(j, j < steps);
+        wait_vmcnt<LPS * (ST - 1)>();           // stage 0
+        __syncthreads();
+        read_stage(0, StepTag<0>{});
+        int nxt = 1;                            // ring slot of the step after the current one
+        auto one_step = [&](int step, auto PAR) __attribute__((always_inline)) {
+            constexpr int cur = decltype(PAR)::value;
+            wait_vmcnt<LPS * (ST - 2)>();       // this wave's loads of step + 1 have landed
+            __syncthreads();                    // ... everyone's have, and nobody reads the slot of `step` any more
+            read_stage(nxt, StepTag<cur ^ 1>{});
+#pragma unroll
+            for (int kk = 0; kk < KI; ++kk)
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Elem<T>::mfma32(bfr[cur][kk][ni], af[cur][kk][mi], acc[mi][ni]);
+            constexpr int NM = KI * MI * NI, NR = KI * (MI + NI), RPM = (NR + NM - 1) / NM;
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);    // LDS reads of the next step
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue(nxt == 0 ? ST - 1 : nxt - 1, step + ST < steps);     // refill the slot of `step`
+            nxt = nxt + 1 == ST ? 0 : nxt + 1;
+        };
+        for (int step = 0; step < steps;) {
+            one_step(step, StepTag<0>{});
+            if (++step < steps) {
+                one_step(step, StepTag<1>{});
+                ++step;
+            }
+        }
+    } else {
 #pragma unroll
     for (int j = 0; j < ST - 1; ++j) issue(j, j < steps);
 
@@ -164,6 +233,7 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
                 for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Elem<T>::mfma32(bfr[kk][ni], af[kk][mi], acc[mi][ni]);
         stage = stage + 1 == ST ? 0 : stage + 1;
         fill = fill + 1 == ST ? 0 : fill + 1;
+    }
     }
     wait_vmcnt<0>();                            // drain the trailing no-op loads before the wave ends
 
@@ -225,13 +295,13 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
     }
 }
 
-template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int ST>
+template <typename T, typename TO, int BM, int BN, int BK, int WM, int WN, int ST, int PF = 0>
 hipError_t launch_dma(const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     constexpr int THREADS = (BM / WM) * (BN / WN) * 64;
     constexpr int LDS_BYTES = ST * (BM + BN) * BK * 2;
     static_assert(LDS_BYTES <= 160 * 1024, "stages do not fit the 160 KiB LDS");
     const int tiles_m = (s.M + BM - 1) / BM, tiles_n = (s.K + BN - 1) / BN;
-    auto kern = igemm_dma_kernel<T, TO, BM, BN, BK, WM, WN, ST>;
+    auto kern = igemm_dma_kernel<T, TO, BM, BN, BK, WM, WN, ST, PF>;
     if (LDS_BYTES > 64 * 1024) {
         // once per kernel and process; a failed attempt is retried by the next call
         static std::atomic<bool> raised{false};
@@ -256,7 +326,8 @@ hipError_t launch_dma(const void* x, const void* w, void* y, const ConvShape& s,
     X(4, "d256x256x32_w128x64_s3", (launch_dma<T, TO, 256, 256, 32, 128, 64, 3>)) \
     X(5, "d64x64x64_w32x32_s4", (launch_dma<T, TO, 64, 64, 64, 32, 32, 4>))       \
     X(6, "d128x128x64_w64x32_s3", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3>))   \
-    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))
+    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))        \
+    X(8, "d128x128x64_w64x32_s3_pf", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3, 1>))
 
 #define X_NAME(i, name, fn) name,
 const char* const kVariantNames[] = {ICONV_VARIANTS(X_NAME)};
@@ -305,7 +376,7 @@ int choose_variant(const ConvShape& s) {
     }
     if (s.K <= 64) return 2;                          // d128x64x64
     if (tiles_256x128 >= 512) return 3;
-    return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 128 ? 6 : 5;
+    return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 128 ? 8 : 5;      // d128x128x64, operands prefetched a step ahead
 }
 
 }  // namespace
