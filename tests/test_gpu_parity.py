@@ -404,3 +404,66 @@ def test_channel_last_rejects_fp32_and_bad_arguments(B):
     with pytest.raises(B.IconvError) as e:
         B.iconv_fwd_channel_last(t, t, None, *L.shape_args(), 1)
     assert e.value.status == -1
+
+
+LARGE = [
+    # name, N, H, W, C, K, R, S, stride, pad, dil: x (and for the last one y) larger than 2^31 bytes
+    ("large_s1", 20, 1024, 1024, 64, 8, 3, 3, 1, 1, 1),
+    ("large_s2", 20, 1024, 1024, 64, 16, 3, 3, 2, 1, 1),
+    ("large_stem", 20, 4096, 4096, 4, 16, 7, 7, 2, 3, 1),
+]
+
+
+@pytest.mark.parametrize("case", LARGE, ids=[c[0] for c in LARGE])
+def test_tensors_beyond_two_gib_against_closed_form(B, case):
+    """Tensors whose byte offsets exceed 2^31 (the ABI allows up to 2^31 - 1 elements).  The oracle
+    cannot run at this size, so the input is x[n,h,w,c] = n % 3 + 1 + h % 2 with all-ones filters:
+    y[n,p,q,k] = C * #{valid s} * sum over valid r of (n % 3 + 1 + h(p, r) % 2), small integers that
+    fp32 accumulates exactly, different for neighbouring images and rows."""
+    name, N, H, W, C, K, R, S, st, pad, dil = case
+    P = (H + 2 * pad - dil * (R - 1) - 1) // st + 1
+    Q = (W + 2 * pad - dil * (S - 1) - 1) // st + 1
+    assert N * H * W * C * 2 > 2 ** 31 and N * H * W * C < 2 ** 31 and N * P * Q * K < 2 ** 31
+    dev = "cuda:0"
+    n_idx = (torch.arange(N, device=dev) % 3 + 1).view(N, 1, 1, 1)
+    h_idx = (torch.arange(H, device=dev) % 2).view(1, H, 1, 1)
+    x = (n_idx + h_idx).to(torch.bfloat16).expand(N, H, W, C).contiguous()
+    w = torch.ones((K, R, S, C), dtype=torch.bfloat16, device=dev)
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device=dev)
+    B.iconv_fwd(x, w, y, N, H, W, C, K, R, S, st, pad, dil, 1)
+    torch.cuda.synchronize()
+    del x
+    rowsum = np.zeros((N, P))
+    for r in range(R):
+        h = np.arange(P) * st + r * dil - pad
+        ok = (h >= 0) & (h < H)
+        rowsum += ok[None, :] * ((np.arange(N) % 3 + 1)[:, None] + (h % 2)[None, :])
+    cols = sum((((np.arange(Q) * st + s_ * dil - pad) >= 0) & ((np.arange(Q) * st + s_ * dil - pad) < W)).astype(np.float64)
+               for s_ in range(S))
+    want = torch.from_numpy((C * rowsum[:, :, None] * cols[None, None, :]).astype(np.float32)).to(dev).view(N, P, Q, 1)
+    bad = int((y != want).sum())
+    assert bad == 0, f"{bad} of {y.numel()} outputs differ from the closed form"
+
+
+def test_side_streams_give_the_same_bits(B):
+    """The stream argument is honoured: two different layers queued on two side streams at once
+    give the bits they give on the default stream (no hidden state is shared between launches)."""
+    layers = [workloads.small_layer("st_a", 4, 28, 28, 64, 64, 3, 3, 1, 1, 1, seed_id=860),      # resident-filter kernel
+              workloads.small_layer("st_b", 2, 30, 30, 128, 160, 3, 3, 2, 1, 1, seed_id=861)]    # per-tap kernel
+    bufs, base = [], []
+    for L in layers:
+        x, w = workloads.make_inputs(L)
+        xd, wd = B.to_device(x, 1), B.to_device(w, 1)
+        y0 = B.empty_output(L.N, L.P, L.Q, L.K, 1)
+        B.iconv_fwd(xd, wd, y0, *L.shape_args(), 1)
+        bufs.append((xd, wd))
+        base.append(y0)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.full_like(b, float("nan")) for b in base]
+    for _ in range(5):
+        for L, (xd, wd), y, st in zip(layers, bufs, outs, streams):
+            B.iconv_fwd(xd, wd, y, *L.shape_args(), 1, stream=st)
+    torch.cuda.synchronize()
+    for y, y0 in zip(outs, base):
+        assert torch.equal(y, y0)
