@@ -12,6 +12,7 @@
 //
 // Tiling follows section 5's block-level scheme: one workgroup per (image, output block,
 // BN filters), no atomics.
+#include <algorithm>
 #include <atomic>
 
 #include "iconv_common.h"
@@ -33,6 +34,10 @@ struct PatchGeom {
     int total_tiles;     // N * tiles_h * tiles_w * tiles_n
     int tiles_per_wg;    // contiguous tiles per workgroup
     float inv_tw;        // 1 / TW
+    // Small feature maps: a tile holds G whole images (TH = P, TW = Q), stacked along the rows: output
+    // row v of the tile is row v % TH of image v / TH, patch row v is row v % PH of image v / PH.
+    int G;               // images per tile (1 unless the whole map fits a tile at least twice)
+    float inv_th, inv_ph;
 };
 
 // Patch swizzle.  The patch is an array of 256-byte windows (all 64 LDS banks), each holding
@@ -75,7 +80,7 @@ template <int BN> __device__ __forceinline__ TileCoord decode_tile(int t, const 
     const int tile_n = t % g.tiles_n; t /= g.tiles_n;
     const int tile_w = t % g.tiles_w; t /= g.tiles_w;
     const int tile_h = t % g.tiles_h;
-    c.n = t / g.tiles_h;
+    c.n = (t / g.tiles_h) * g.G;
     c.p0 = tile_h * g.TH; c.q0 = tile_w * g.TW; c.k0 = tile_n * BN;
     return c;
 }
@@ -172,11 +177,12 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         };
         // one patch load (or a no-op load into the sink once the phase's patch is complete)
         auto patch_load = [&](bool allowed) {
-            const int h = a_hb + a_ph, ww = a_wb + a_pw;
+            const int gi = g.G > 1 ? (int)(((float)a_ph + 0.5f) * g.inv_ph) : 0;     // image of the tile this patch row belongs to
+            const int h = a_hb + a_ph - gi * g.PH, ww = a_wb + a_pw;
             const bool real = allowed && a_live && a_j < g.a_blocks;   // wave-uniform
-            const bool ok = real & (a_ph < g.PH) & ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W) &
-                            ((a_c0 + a_lc) < s.C);
-            const uint32_t off = (uint32_t)(((a_n * s.H + h) * s.W + ww) * s.C + a_c0 + a_lc) * 2u;
+            const bool ok = real & (a_ph < g.G * g.PH) & (a_n + gi < s.N) & ((unsigned)h < (unsigned)s.H) &
+                            ((unsigned)ww < (unsigned)s.W) & ((a_c0 + a_lc) < s.C);
+            const uint32_t off = (uint32_t)((((a_n + gi) * s.H + h) * s.W + ww) * s.C + a_c0 + a_lc) * 2u;
             const uint32_t dst = real ? lds_base + (uint32_t)a_buf * g.patch_bytes + (uint32_t)(lw + a_j * NLD) * 1024u : sink;
             dma16(x_rsrc, ok ? off : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
             a_pw += g.dpw;
@@ -331,17 +337,20 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     // =============================== compute waves ==============================================
     const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
     const int frow = lane & 31, fk = lane >> 5;
-    const int npx = g.TH * g.TW;
+    const int npx = g.G * g.TH * g.TW;
     int a_base[MI];                             // patch pixel of each A-fragment row at tap (0, 0)
-    int o_th[MI], o_tw[MI];                     // the same row as (row, column) of the output block
+    int o_th[MI], o_tw[MI], o_gi[MI];           // the same row as (row, column) of the output block, and its image within the tile
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int t = (wave_m * MI + mi) * 32 + frow;
-        const int th = (int)(((float)t + 0.5f) * g.inv_tw);
-        const int tw = t - th * g.TW;
-        a_base[mi] = t < npx ? (th * g.PW + tw) * s.stride : 0;
+        const int tv = (int)(((float)t + 0.5f) * g.inv_tw);                 // row of the stacked tile
+        const int tw = t - tv * g.TW;
+        const int gi = g.G > 1 ? (int)(((float)tv + 0.5f) * g.inv_th) : 0;
+        const int th = tv - gi * g.TH;
+        a_base[mi] = t < npx ? ((gi * g.PH + th * s.stride) * g.PW + tw * s.stride) : 0;
         o_th[mi] = t < npx ? th : (1 << 20);    // rows past the block never pass the p < P test
         o_tw[mi] = tw;
+        o_gi[mi] = gi;
     }
     int b_idx[NI][KI];                          // filter-fragment positions within a stage (16-byte units)
 #pragma unroll
@@ -363,7 +372,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         // end after its last step: once every compute wave is here LDS is free, and the fragments go
         // through wave-private staging areas so that each store covers whole 128-byte lines.  (A
         // barrier counts live waves only, so the ended loader waves do not take part.)
-        if (SS == 0 && tile == t_end - 1 && vec_ok && (long long)g.TH * s.Q * s.K * (long long)sizeof(TO) < 0x7fffffffLL) {
+        if (SS == 0 && tile == t_end - 1 && vec_ok && (long long)g.G * g.TH * s.Q * s.K * (long long)sizeof(TO) < 0x7fffffffLL) {
             __syncthreads();
             char* stg = reinterpret_cast<char*>(lds) + wave * kFragStageBytes;
             const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
@@ -378,19 +387,21 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                     const bool pieces_ok = col0 + 4 * (lane & 7) + 3 < s.K;
                     store_frag_staged<TO>(stg, acc[mi][ni], lane, y_rsrc, pieces_ok, [&](int i) {
                         const int t = (wave_m * MI + mi) * 32 + i;
-                        const int th = (int)(((float)t + 0.5f) * g.inv_tw);
-                        const int tw = t - th * g.TW;
-                        const bool ok = (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q);
-                        return ok ? (uint32_t)((th * s.Q + tw) * s.K + col0) * (uint32_t)sizeof(TO) : 0x80000000u;
+                        const int tv = (int)(((float)t + 0.5f) * g.inv_tw);
+                        const int tw = t - tv * g.TW;
+                        const int gi = g.G > 1 ? (int)(((float)tv + 0.5f) * g.inv_th) : 0;
+                        const int th = tv - gi * g.TH;
+                        const bool ok = (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q) & (tc.n + gi < s.N);
+                        return ok ? (uint32_t)(((gi * s.P + th) * s.Q + tw) * s.K + col0) * (uint32_t)sizeof(TO) : 0x80000000u;
                     });
                 }
             return;
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi];
-            if (p < s.P && q < s.Q) {
-                TO* yrow = y + (size_t)((tc.n * s.P + p) * s.Q + q) * s.K;
+            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi], n = tc.n + o_gi[mi];
+            if (p < s.P && q < s.Q && n < s.N) {
+                TO* yrow = y + (size_t)((n * s.P + p) * s.Q + q) * s.K;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
@@ -670,7 +681,29 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
             g->inv_tw = 1.0f / (float)tw;
         }
     }
-    return found;
+    if (!found) return false;
+    g->G = 1;
+    g->inv_th = 1.0f / (float)g->TH;
+    g->inv_ph = 1.0f / (float)g->PH;
+    // A map that fits a tile at least twice (the 7 x 7 maps at the end of a network): several whole
+    // images per tile, as many as the rows and LDS hold.  The filter tile of a step then serves all of
+    // them, and the filter traffic per output, which is what binds these layers, drops accordingly.
+    if (c.ss == 0 && g->TH == s.P && g->TW == s.Q) {
+        const int per_pass = rpb * c.nld;
+        for (int G = std::min(BM / (s.P * s.Q), s.N); G >= 2; --G) {
+            const long npix = (long)G * g->PH * g->PW;
+            const int a_blocks = (int)((npix + per_pass - 1) / per_pass);
+            const long patch_bytes = (long)a_blocks * c.nld * 1024;
+            const long lds = 2 * patch_bytes + (long)c.stb * c.bn() * c.cb * 2 + c.nld * 1024 + c.tail_bytes();
+            if (lds > kLdsLimit || (long)c.la * (RS - c.stb + 1) < a_blocks) continue;
+            g->G = G;
+            g->npix = (int)npix;
+            g->a_blocks = a_blocks;
+            g->patch_bytes = (int)patch_bytes;
+            break;
+        }
+    }
+    return true;
 }
 
 template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
@@ -686,7 +719,7 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
         if (e != hipSuccess) return e;
         raised.store(true, std::memory_order_release);
     }
-    const long total = (long)s.N * g.tiles_h * g.tiles_w * g.tiles_n;
+    const long total = (long)((s.N + g.G - 1) / g.G) * g.tiles_h * g.tiles_w * g.tiles_n;
     if (total > 0x7fffffffL) return hipErrorInvalidConfiguration;
     // resident workgroups per compute unit for this LDS size (cached per kernel and size)
     static std::atomic<long long> occ_slot{-1};

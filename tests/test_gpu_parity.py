@@ -467,3 +467,26 @@ def test_side_streams_give_the_same_bits(B):
     torch.cuda.synchronize()
     for y, y0 in zip(outs, base):
         assert torch.equal(y, y0)
+
+
+def test_tiles_holding_several_images(B):
+    """Small feature maps: the patch-reuse kernels put several whole images into one tile.  Odd image
+    counts (a last tile with fewer images), maps of 7 x 7, 5 x 6 and 1 x 1 pixels, padding, dilation,
+    ragged channels and filters, every patch-reuse kernel forced, uncapped and with one or three
+    workgroups walking through all tiles."""
+    shapes = [workloads.small_layer("g_a", 5, 7, 7, 136, 160, 3, 3, 1, 1, 1, seed_id=870),
+              workloads.small_layer("g_b", 7, 5, 6, 64, 72, 3, 3, 1, 1, 1, dtype="f16", seed_id=871),
+              workloads.small_layer("g_c", 9, 3, 3, 128, 64, 3, 3, 1, 0, 1, seed_id=872),            # P = Q = 1
+              workloads.small_layer("g_d", 3, 9, 9, 64, 136, 3, 3, 1, 2, 2, seed_id=873)]           # dilated
+    names = [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
+    try:
+        for cap in (0, 1, 3):
+            B.iconv_set_max_workgroups(cap)
+            for v in [-1] + [i for i, nm in enumerate(names) if nm.startswith("p")]:
+                B.iconv_set_variant(v)
+                for L in shapes:
+                    print("cap", cap, "variant", names[v] if v >= 0 else "auto", L.name, flush=True)
+                    check(B, L)
+    finally:
+        B.iconv_set_variant(-1)
+        B.iconv_set_max_workgroups(0)
