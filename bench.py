@@ -69,8 +69,9 @@ def main():
     torch.cuda.set_device(0)
     B.iconv_set_variant(args.variant)
 
-    def time_steps(fn, steps, warmup):
-        """ms per step over exactly `steps` steps after `warmup` untimed ones."""
+    def time_steps(fn, steps, warmup, repeats=1):
+        """ms per step over exactly `steps` steps after `warmup` untimed ones; with repeats > 1 the graph of
+        `steps` launches is replayed that many times and the median replay is reported."""
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
@@ -90,11 +91,15 @@ def main():
                 for _ in range(steps):
                     fn()
         torch.cuda.synchronize()
-        e0.record()
-        graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps
+        times = []
+        for _ in range(max(1, repeats)):
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) / steps)
+        times.sort()
+        return times[len(times) // 2]
 
     def prepare(L):
         code = B.DTYPE_CODES[L.dtype]
@@ -185,7 +190,7 @@ def main():
         for name, Li in workloads.LAYERS.items():
             _, _, ri, keep = prepare(Li)
             n = max(50, args.steps // 10)
-            mi = time_steps(ri, n, max(20, args.warmup // 4))
+            mi = time_steps(ri, n, max(20, args.warmup // 4), repeats=5)       # median of five replays of n launches
             bi, tf, gb = bound_of(Li, mi)
             tf_real = Li.flops_real / (mi * 1e-3) / 1e12
             layers[name] = {"us": round(mi * 1e3, 3), "tflops": round(tf_real, 2), "bound": bi,
@@ -203,7 +208,7 @@ def main():
             xd, wd = B.to_device(x, c), B.to_device(w, c)
             y = B.empty_output(Li.N, Li.P, Li.Q, Li.K, c)
             sa = Li.shape_args()
-            t = time_steps(lambda: B.iconv_fwd(xd, wd, y, *sa, c), 100, 20)
+            t = time_steps(lambda: B.iconv_fwd(xd, wd, y, *sa, c), 100, 20, repeats=5)
             del xd, wd, y
             torch.cuda.empty_cache()
             return t
