@@ -55,8 +55,8 @@ def main():
                     help="add the stride/dilation sensitivity table, the batch 8/64 sweep and the output-type table")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (a batch-sharded forward convolution needs no exchange "
-              "step; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (a forward convolution shards over the batch with no exchange "
+              "step, so more GPUs would only run copies of this). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
