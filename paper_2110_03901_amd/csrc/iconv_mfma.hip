@@ -23,6 +23,10 @@ namespace {
 // The loads are emitted as inline assembly on purpose: the compiler then does not pair every
 // later LDS read with a wait for *all* outstanding loads, and the kernel places its own
 // s_waitcnt vmcnt(n) so that the loads of the next ST-2 steps stay in flight during a step.
+//
+// PF = 1: the operand fragments of step i + 1 are read from LDS between the MFMAs of step i, and
+// the fragment registers act as one more stage.  The epilogue goes through wave-private LDS
+// staging areas (the stages are free by then), so that every store covers whole 128-byte lines.
 // ---------------------------------------------------------------------------------------------
 template <int V> struct StepTag { static constexpr int value = V; };
 

@@ -11,7 +11,9 @@
 // R*S / ((PH*PW)/(TH*TW)); the filter tile of each step still streams through a small ring.
 //
 // Tiling follows section 5's block-level scheme: one workgroup per (image, output block,
-// BN filters), no atomics.
+// BN filters), no atomics.  A feature map that fits a tile at least twice is stacked: the tile
+// then holds several whole images, their patches one below the other in LDS, so that the small
+// maps at the end of a network fill the rows of the MFMA tiles.
 #include <algorithm>
 #include <atomic>
 
@@ -70,7 +72,14 @@ struct PatchGeom {
 // from the compute waves' next deposit; the last tile is drained after one extra barrier at the
 // end.  Store waves are separate from loader waves because a wave that counts outstanding loads
 // with s_waitcnt vmcnt must not have stores in flight as well: stores need not retire in order
-// with loads.
+// with loads.  The last tile of a workgroup, whose stores nothing can hide, leaves through
+// wave-private LDS staging areas instead, so that every store covers whole 128-byte lines.
+//
+// Prefetching variants (PF).  A wave issues in order, so only what sits between two of its
+// MFMAs runs in their shadow.  With PF the operand fragments of the next group of K slices, and
+// the addresses of the next step, are requested between the MFMAs of the current group, across
+// the step barrier too; the loaders then keep the NEXT step's filter tile complete at every
+// barrier, and the fragment registers act as one more stage of the ring.
 struct TileCoord {
     int n, p0, q0, k0;
 };
