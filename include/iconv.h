@@ -27,7 +27,8 @@
  * bias, one group).  The library allocates nothing, frees nothing and never synchronises: the
  * kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream)
  * and the results are valid once the caller has synchronised that stream.  Calls are
- * thread-safe; there is no mutable global state.
+ * thread-safe; the only mutable global state is the pair of benchmarking overrides at the end
+ * of this header (kernel choice, workgroup cap), which ordinary callers leave alone.
  *
  * Errors are reported by the return value only (never abort, never throw):
  */
