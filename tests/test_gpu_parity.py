@@ -490,3 +490,37 @@ def test_tiles_holding_several_images(B):
     finally:
         B.iconv_set_variant(-1)
         B.iconv_set_max_workgroups(0)
+
+
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        N = int(rng.integers(1, 6)); H = int(rng.integers(1, 41)); W = int(rng.integers(1, 41))
+        C = int(rng.choice([4, 8, 16, 24, 32, 40, 64, 72, 128, 136])); K = int(rng.integers(1, 201))
+        R = int(rng.choice([1, 2, 3, 5])); S = int(rng.choice([1, 2, 3, 5, 7]))
+        stride = int(rng.choice([1, 1, 2, 3])); pad = int(rng.integers(0, 4)); dil = int(rng.choice([1, 1, 2]))
+        P = (H + 2 * pad - dil * (R - 1) - 1) // stride + 1 if H + 2 * pad - dil * (R - 1) - 1 >= 0 else 0
+        Q = (W + 2 * pad - dil * (S - 1) - 1) // stride + 1 if W + 2 * pad - dil * (S - 1) - 1 >= 0 else 0
+        if P < 1 or Q < 1:
+            continue
+        out.append((N, H, W, C, K, R, S, stride, pad, dil))
+    return out
+
+
+def test_random_shapes_through_the_default_choice_and_forced_kernels(B):
+    """Seeded random layer shapes (odd sizes, filters wider than the map allows without padding,
+    1 x S and R x 1 filters, K not a multiple of four) through the library's own kernel choice, and
+    a third of them through every patch-reuse and per-tap kernel that accepts them."""
+    shapes = _random_shapes(48, 20211)
+    names = [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
+    try:
+        for i, dims in enumerate(shapes):
+            L = workloads.small_layer(f"rnd{i}", *dims, dtype="bf16" if i % 2 == 0 else "f16", seed_id=900 + i)
+            forced = [-1] + (list(range(len(names))) if i % 3 == 0 and L.C % 8 == 0 else [])
+            for v in forced:
+                B.iconv_set_variant(v)
+                print("shape", dims, "variant", names[v] if v >= 0 else "auto", flush=True)
+                check(B, L)
+    finally:
+        B.iconv_set_variant(-1)
