@@ -469,6 +469,48 @@ def test_side_streams_give_the_same_bits(B):
         assert torch.equal(y, y0)
 
 
+def test_graph_replays_match_eager_runs(B):
+    """The timed configuration is a HIP-graph replay: one graph holding a launch of each kernel family
+    (resident-filter, patch-reuse with staged output, per-tap, merged-tap stem, fp32 direct) is
+    replayed four times, with new inputs written eagerly into the same buffers and a device
+    synchronisation between replays; every replay must give the bits of the eager call on those inputs."""
+    layers = [(workloads.small_layer("gr_res", 4, 28, 28, 64, 64, 3, 3, 1, 1, 1, seed_id=870), 1),
+              (workloads.small_layer("gr_patch", 2, 24, 24, 64, 128, 3, 3, 1, 2, 2, seed_id=871), 1),
+              (workloads.small_layer("gr_tap", 2, 30, 30, 128, 160, 3, 3, 2, 1, 1, seed_id=872), 3),
+              (workloads.small_layer("gr_stem", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1, seed_id=873), 1),
+              (workloads.small_layer("gr_f32", 1, 9, 9, 5, 7, 3, 3, 1, 1, 1, dtype="f32", seed_id=874), 0)]
+    bufs = []
+    for L, code in layers:
+        x, w = workloads.make_inputs(L)
+        bufs.append((B.to_device(x, code), B.to_device(w, code), B.empty_output(L.N, L.P, L.Q, L.K, code)))
+    for (L, code), (xd, wd, y) in zip(layers, bufs):               # warm up outside the capture
+        B.iconv_fwd(xd, wd, y, *L.shape_args(), code)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for (L, code), (xd, wd, y) in zip(layers, bufs):
+                B.iconv_fwd(xd, wd, y, *L.shape_args(), code, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        fresh = []
+        for (L, code), (xd, wd, y) in zip(layers, bufs):
+            x, _ = workloads.make_inputs(L, seed_offset=100 + rep)
+            xd.copy_(B.to_device(x, code))
+            want = torch.full_like(y, float("nan"))
+            B.iconv_fwd(xd, wd, want, *L.shape_args(), code)
+            fresh.append(want)
+            y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for (L, _), (_, _, y), want in zip(layers, bufs, fresh):
+            assert torch.isfinite(y.float()).all(), f"{L.name}: replay {rep} left outputs unwritten"
+            assert torch.equal(y, want), f"{L.name}: replay {rep} differs from the eager run"
+
+
 def test_tiles_holding_several_images(B):
     """Small feature maps: the patch-reuse kernels put several whole images into one tile.  Odd image
     counts (a last tile with fewer images), maps of 7 x 7, 5 x 6 and 1 x 1 pixels, padding, dilation,
