@@ -443,11 +443,17 @@ bool resident_supported(const ConvShape& s, int v) {
 
 // The variant with the lower modelled cost, or -1 when the layer does not fit the kernel.
 // Its blocks are large (448 or 512 pixels x all filters), so it is only offered when there are
-// enough of them to occupy most of the device.
+// enough of them to occupy most of the device -- or half of it, when the 256-pixel tiles of the
+// patch-reuse kernel that would run instead no longer fit one round of workgroups (measured on the
+// 56 x 56, 64 -> 64 layer: batches 20 .. 27 take 13.2 .. 14.3 us here against 16.6 us there).
 int resident_choose(const ConvShape& s) {
     ResGeom g7, g8;
     double c7 = 0, c8 = 0;
-    const long enough = (long)device_cus() * 3 / 4;
+    const long cus = device_cus();
+    // full-width tiles of 256 / Q output rows, as the patch-reuse planner forms them for narrow maps
+    const long th = s.Q <= 256 ? 256 / s.Q : 1;
+    const long patch_tiles = (long)s.N * ((s.P + th - 1) / th) * ((s.Q + 255) / 256);
+    const long enough = patch_tiles > cus ? cus / 2 : cus * 3 / 4;
     const bool ok7 = plan_res(s, 7, &g7, &c7) && g7.total_tiles >= enough;
     const bool ok8 = plan_res(s, 8, &g8, &c8) && g8.total_tiles >= enough;
     if (!ok7 && !ok8) return -1;
