@@ -365,8 +365,11 @@ int choose_variant(const ConvShape& s) {
     }
     if (s.R * s.S > 1 && s.stride == 1) {
         int v;
+        const long tiles_256x64 = (long)((s.M + 255) / 256) * ((s.K + 63) / 64);
         if (s.K <= 64) v = P0 + 5;                    // p256x64, eight compute waves of 32x64
-        else if (tiles_256x128 >= 200) v = P0 + 17;   // p256x128, operands prefetched one group of K slices ahead
+        else if (tiles_256x128 >= 190)                // p256x128; with many channel chunks per tap, operands prefetched
+            v = s.C >= 256 ? P0 + 17 : P0 + 3;        // one group of K slices ahead
+        else if (tiles_256x64 >= 190) v = P0 + 5;     // p256x64 when that still gives most compute units a tile
         else if (s.C % 128 == 0) v = P0 + 20;         // p64x128 (many small tiles), 128-channel chunks: half the steps
         else v = P0 + 19;                             // p64x128, prefetching
         if (patch_supported(s, v - P0)) return v;
@@ -374,9 +377,10 @@ int choose_variant(const ConvShape& s) {
     }
     if (s.R * s.S == 1) {
         const long tiles_256x256 = (long)((s.M + 255) / 256) * ((s.K + 255) / 256);
-        if (tiles_256x256 >= 160) return 4;           // d256x256x32
-        if (tiles_256x128 >= 160) return 3;           // d256x128x64
-        return s.K <= 64 ? 2 : 6;
+        if (s.K > 128 && tiles_256x256 >= 160) return 4;   // d256x256x32
+        if (tiles_256x128 >= 160) return 3;                // d256x128x64
+        if (s.K <= 64) return 2;                           // d128x64x64
+        return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 160 ? 6 : 5;    // d128x128x64, else d64x64x64
     }
     if (s.K <= 64) return 2;                          // d128x64x64
     if (tiles_256x128 >= 512) return 3;
