@@ -9,6 +9,7 @@
 
 #include "iconv_common.h"
 #include "iconv_device.h"
+#include "iconv_host.h"
 
 namespace iconv {
 
@@ -366,7 +367,8 @@ int choose_variant(const ConvShape& s) {
     if (s.R * s.S > 1 && s.stride == 1) {
         int v;
         const long tiles_256x64 = (long)((s.M + 255) / 256) * ((s.K + 63) / 64);
-        if (s.K <= 64) v = P0 + 5;                    // p256x64, eight compute waves of 32x64
+        if (s.K <= 64)                                // p256x64 (eight compute waves of 32x64), p128x64 or p64x64
+            v = (s.M + 255) / 256 >= 128 ? P0 + 5 : (s.M + 127) / 128 >= 128 ? P0 + 1 : P0 + 7;
         else if (tiles_256x128 >= 190)                // p256x128; with many channel chunks per tap, operands prefetched
             v = s.C >= 256 ? P0 + 17 : P0 + 3;        // one group of K slices ahead
         else if (tiles_256x64 >= 190) v = P0 + 5;     // p256x64 when that still gives most compute units a tile
@@ -383,8 +385,11 @@ int choose_variant(const ConvShape& s) {
         return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 160 ? 6 : 5;    // d128x128x64, else d64x64x64
     }
     if (s.K <= 64) return 2;                          // d128x64x64
-    if (tiles_256x128 >= 512) return 3;
-    return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 128 ? 8 : 5;      // d128x128x64, operands prefetched a step ahead
+    const long tiles_128x128 = (long)((s.M + 127) / 128) * ((s.K + 127) / 128);
+    // d128x128x64 (operands prefetched a step ahead) while its tiles fit one round of workgroups; d256x128x64 when
+    // they do not and the larger tiles still reach half the compute units; d64x64x64 for very small outputs
+    if (tiles_128x128 > device_cus() && tiles_256x128 >= device_cus() / 2) return 3;
+    return tiles_128x128 >= 128 ? 8 : 5;
 }
 
 }  // namespace
