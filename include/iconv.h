@@ -129,6 +129,15 @@ int iconv_set_variant(int variant);
 int iconv_num_variants(void);
 const char *iconv_variant_name(int variant);
 
+/* Which kernel iconv_fwd runs for a layer when no override is set: the name of a kernel-table
+ * entry (iconv_variant_name), "stem" for the merged-tap kernel of 4-channel first layers (the
+ * multi-tile idea of section 4.3) or "direct" for the plain kernel.  Host logic only: no device
+ * work, no pointers; the choice depends on the tile counts of the block-level decomposition of
+ * section 5 against the number of compute units (256 is assumed when no device is present).
+ * Returns a static string, or NULL for arguments iconv_fwd would reject (shape, dtype, size). */
+const char *iconv_kernel_for(int N, int H, int W, int C, int K, int R, int S,
+                             int stride, int pad, int dilation, int dtype);
+
 /* Test and measurement hook for the persistent kernels: n > 0 caps the number of workgroups a
  * launch uses (each then walks through more output tiles), 0 restores the default of filling
  * the device.  Process-wide, not thread-safe.  Returns ICONV_ERR_UNSUPPORTED for n < 0. */

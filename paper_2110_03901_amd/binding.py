@@ -52,11 +52,13 @@ _lib.iconv_set_max_workgroups.argtypes = [_i]
 _lib.iconv_num_variants.restype = _i
 _lib.iconv_variant_name.restype = ctypes.c_char_p
 _lib.iconv_variant_name.argtypes = [_i]
+_lib.iconv_kernel_for.restype = ctypes.c_char_p
+_lib.iconv_kernel_for.argtypes = [_i] * 11
 _lib.iconv_status_string.restype = ctypes.c_char_p
 _lib.iconv_status_string.argtypes = [_i]
 
 EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
-           "iconv_probe_copy", "iconv_probe_mfma", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name",
+           "iconv_probe_copy", "iconv_probe_mfma", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name", "iconv_kernel_for",
            "iconv_status_string"]
 
 
@@ -171,6 +173,12 @@ def iconv_num_variants() -> int:
 
 def iconv_variant_name(variant: int) -> str:
     return _lib.iconv_variant_name(variant).decode()
+
+
+def iconv_kernel_for(N, H, W, C, K, R, S, stride, pad, dilation, dtype):
+    """Name of the kernel iconv_fwd runs for this layer without an override, or None for invalid arguments."""
+    r = _lib.iconv_kernel_for(N, H, W, C, K, R, S, stride, pad, dilation, dtype)
+    return r.decode() if r is not None else None
 
 
 # ---- device-buffer helpers (plumbing: upload, allocate, download) ---------------------------

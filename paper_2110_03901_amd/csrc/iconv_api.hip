@@ -162,6 +162,17 @@ int iconv_probe_mfma(void* out, size_t out_bytes, int iters, int random_operands
     return status_of(launch_mfma_probe(out, iters, random_operands != 0, (hipStream_t)stream));
 }
 
+const char* iconv_kernel_for(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dilation, int dtype) {
+    int in_t, out_t;
+    ConvShape s;
+    if (!dtype_types(dtype, &in_t, &out_t)) return nullptr;
+    if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK) return nullptr;
+    // same order as run_conv
+    if (in_t != IN_F32 && (s.C % 8) == 0) return mfma_variant_name(mfma_default_variant(s));
+    if (in_t != IN_F32 && stem_supported(s)) return "stem";
+    return "direct";
+}
+
 int iconv_set_variant(int variant) {
     if (variant < -1 || variant >= mfma_num_variants()) return ICONV_ERR_UNSUPPORTED;
     g_variant.store(variant);

@@ -58,6 +58,7 @@ hipError_t launch_direct(const void* x, const void* w, void* y, const ConvShape&
 
 int mfma_num_variants();
 const char* mfma_variant_name(int v);
+int mfma_default_variant(const ConvShape& s);   // kernel-table entry chosen without an override (C % 8 == 0 layers)
 // Picks a tile variant (or uses `variant` when >= 0) and launches the implicit-GEMM kernel.
 // Requires C % 8 == 0 and a 16-bit input type.
 hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,

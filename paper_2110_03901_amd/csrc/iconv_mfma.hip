@@ -403,6 +403,8 @@ const char* mfma_variant_name(int v) {
     return resident_variant_name(v - kNumVariants - patch_num_variants());
 }
 
+int mfma_default_variant(const ConvShape& s) { return choose_variant(s); }
+
 hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int variant,
                        hipStream_t st) {
     const int R0 = kNumVariants + patch_num_variants();        // first resident-filter variant

@@ -83,3 +83,43 @@ def test_status_strings_and_variants(lib):
     n = lib.iconv_num_variants()
     assert n >= 1 and len({lib.iconv_variant_name(i) for i in range(n)}) == n
     assert lib.iconv_set_variant(n) == -3 and lib.iconv_set_variant(-1) == 0
+
+
+def kernel_for(lib, *args):
+    lib.iconv_kernel_for.restype = ctypes.c_char_p
+    lib.iconv_kernel_for.argtypes = [ctypes.c_int] * 11
+    r = lib.iconv_kernel_for(*args)
+    return None if r is None else r.decode()
+
+
+def test_kernel_choice_follows_the_layer_class(lib):
+    """iconv_kernel_for (host logic; 256 compute units are assumed without a device): each class of layer gets the
+    kernel family built for it, every answer is a kernel-table name or "stem"/"direct", invalid arguments give NULL."""
+    lib.iconv_variant_name.restype = ctypes.c_char_p
+    table = {lib.iconv_variant_name(i).decode() for i in range(lib.iconv_num_variants())}
+    bf16 = 1
+    # the benchmark layers: resident filters (r...), per-tap direct-to-LDS (d...), patch reuse (p...), merged taps
+    assert kernel_for(lib, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("r")
+    assert kernel_for(lib, 32, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d128x128")
+    assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("d256x256")
+    assert kernel_for(lib, 8, 64, 64, 256, 256, 3, 3, 1, 2, 2, bf16).startswith("p256x128")
+    assert kernel_for(lib, 64, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16).startswith("p64x128_c128")
+    assert kernel_for(lib, 64, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem"
+    assert kernel_for(lib, 1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 0) == "direct"            # fp32
+    assert kernel_for(lib, 2, 8, 8, 20, 16, 3, 3, 1, 1, 1, bf16) == "direct"         # C % 8 != 0
+    # tile size follows the tile count: the same layers at other batch sizes
+    assert kernel_for(lib, 8, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("p128x64")      # 196 tiles of 128 pixels
+    assert kernel_for(lib, 16, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("p256x64")     # 112 resident blocks: too few
+    assert kernel_for(lib, 20, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("r")           # patch tiles need two rounds
+    assert kernel_for(lib, 64, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d256x128")  # 392 tiles of 128x128
+    assert kernel_for(lib, 32, 56, 56, 256, 128, 1, 1, 1, 0, 1, bf16).startswith("d256x128")  # K = 128: no 256-wide tile
+    assert kernel_for(lib, 32, 7, 7, 2048, 512, 1, 1, 1, 0, 1, bf16).startswith("d64x64")     # 1568 output pixels
+    for args in [(3, 17, 19, 8, 8, 1, 1, 1, 0, 1, 2), (5, 9, 33, 48, 24, 5, 3, 2, 2, 1, 3), (1, 1, 1, 8, 1, 1, 1, 1, 0, 1, 4),
+                 (2, 40, 40, 96, 200, 3, 3, 1, 4, 4, bf16), (7, 12, 12, 64, 64, 3, 3, 1, 1, 1, bf16)]:
+        name = kernel_for(lib, *args)
+        assert name in table or name in ("stem", "direct"), (args, name)
+    # what iconv_fwd rejects
+    assert kernel_for(lib, 0, 8, 8, 16, 16, 3, 3, 1, 1, 1, bf16) is None             # shape
+    assert kernel_for(lib, 1, 2, 2, 16, 16, 3, 3, 1, 0, 1, bf16) is None             # empty output
+    assert kernel_for(lib, 1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 9) is None                # dtype
+    assert kernel_for(lib, 4096, 1024, 1024, 8, 8, 1, 1, 1, 0, 1, bf16) is None      # 2^31 elements or more
