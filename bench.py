@@ -67,7 +67,6 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    B.iconv_set_variant(args.variant)
 
     def time_steps(fn, steps, warmup, repeats=1):
         """ms per step over exactly `steps` steps after `warmup` untimed ones; with repeats > 1 the graph of
@@ -107,6 +106,8 @@ def main():
         xd, wd = B.to_device(x, code), B.to_device(w, code)
         y = B.empty_output(L.N, L.P, L.Q, L.K, code)
         sa = L.shape_args()
+        if args.variant >= 0:
+            return code, (x, w), (lambda: B.iconv_fwd_ex(xd, wd, y, *sa, code, args.variant, 0)), (xd, wd, y)
         return code, (x, w), (lambda: B.iconv_fwd(xd, wd, y, *sa, code)), (xd, wd, y)
 
     def bound_of(L, ms):

@@ -27,8 +27,10 @@
  * bias, one group).  The library allocates nothing, frees nothing and never synchronises: the
  * kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream)
  * and the results are valid once the caller has synchronised that stream.  Calls are
- * thread-safe; the only mutable global state is the pair of benchmarking overrides at the end
- * of this header (kernel choice, workgroup cap), which ordinary callers leave alone.
+ * thread-safe: every entry point is a function of its arguments alone, and the library keeps
+ * no mutable state beyond one-time, idempotent caches of device properties (number of compute
+ * units, LDS limits raised once per kernel).  Measurement helpers and the per-call kernel
+ * override used by tests and sweeps live in iconv_bench.h, not here.
  *
  * Errors are reported by the return value only (never abort, never throw):
  */
@@ -107,41 +109,14 @@ int iconv_im2col(const void *x_nhwc, void *workspace, size_t workspace_bytes,
                  int N, int H, int W, int C, int R, int S,
                  int stride, int pad, int dilation, int dtype, void *stream);
 
-/* Measurement helper: a plain device-to-device copy kernel of `bytes` bytes (multiple of 16,
- * both pointers 16-byte aligned), used to calibrate memory-traffic counters and to measure
- * the achievable copy bandwidth. */
-int iconv_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/* Measurement helper: a register-only loop of `iters` x 8 bf16 32x32x16 MFMAs per wave on
- * 1024 workgroups of four waves (no memory traffic in the loop), for the achievable matrix-core
- * rate: 1024 * 4 * iters * 8 * 32768 flop per launch.  random_operands = 0 multiplies one fixed
- * pair of small-integer operands (few bits toggle, the highest clock the chip sustains);
- * random_operands != 0 alternates four pairs of pseudo-random operands, the rate the matrix cores
- * sustain on real data under the board's power limit.  `out` is a device buffer of at least
- * 1024 * 256 * 4 bytes that receives one float per thread (so that the loop is not optimised
- * away).  Returns ICONV_ERR_NULL, ICONV_ERR_SHAPE (iters < 1), ICONV_ERR_WORKSPACE (out too small). */
-int iconv_probe_mfma(void *out, size_t out_bytes, int iters, int random_operands, void *stream);
-
-/* Tile-selection override for sweeps: -1 (default) lets the library choose, other values pick
- * entry `variant` of the kernel table (see iconv_variant_name).  Process-wide, not
- * thread-safe; meant for benchmarking only.  Returns ICONV_ERR_UNSUPPORTED if out of range. */
-int iconv_set_variant(int variant);
-int iconv_num_variants(void);
-const char *iconv_variant_name(int variant);
-
-/* Which kernel iconv_fwd runs for a layer when no override is set: the name of a kernel-table
- * entry (iconv_variant_name), "stem" for the merged-tap kernel of 4-channel first layers (the
+/* Which kernel iconv_fwd runs for a layer: the name of a kernel-table entry (see
+ * iconv_variant_name in iconv_bench.h), "stem" for the merged-tap kernel of 4-channel first layers (the
  * multi-tile idea of section 4.3) or "direct" for the plain kernel.  Host logic only: no device
  * work, no pointers; the choice depends on the tile counts of the block-level decomposition of
  * section 5 against the number of compute units (256 is assumed when no device is present).
  * Returns a static string, or NULL for arguments iconv_fwd would reject (shape, dtype, size). */
 const char *iconv_kernel_for(int N, int H, int W, int C, int K, int R, int S,
                              int stride, int pad, int dilation, int dtype);
-
-/* Test and measurement hook for the persistent kernels: n > 0 caps the number of workgroups a
- * launch uses (each then walks through more output tiles), 0 restores the default of filling
- * the device.  Process-wide, not thread-safe.  Returns ICONV_ERR_UNSUPPORTED for n < 0. */
-int iconv_set_max_workgroups(int n);
 
 /* Static string for a status code. */
 const char *iconv_status_string(int status);

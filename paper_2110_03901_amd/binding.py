@@ -45,11 +45,11 @@ _lib.iconv_probe_copy.restype = _i
 _lib.iconv_probe_copy.argtypes = [_p, _p, _sz, _p]
 _lib.iconv_probe_mfma.restype = _i
 _lib.iconv_probe_mfma.argtypes = [_p, _sz, _i, _i, _p]
-_lib.iconv_set_variant.restype = _i
-_lib.iconv_set_variant.argtypes = [_i]
-_lib.iconv_set_max_workgroups.restype = _i
-_lib.iconv_set_max_workgroups.argtypes = [_i]
+_lib.iconv_fwd_ex.restype = _i
+_lib.iconv_fwd_ex.argtypes = [_p, _p, _p] + [_i] * 13 + [_p]
 _lib.iconv_num_variants.restype = _i
+_lib.iconv_variant_accepts.restype = _i
+_lib.iconv_variant_accepts.argtypes = [_i] * 12
 _lib.iconv_variant_name.restype = ctypes.c_char_p
 _lib.iconv_variant_name.argtypes = [_i]
 _lib.iconv_kernel_for.restype = ctypes.c_char_p
@@ -57,9 +57,10 @@ _lib.iconv_kernel_for.argtypes = [_i] * 11
 _lib.iconv_status_string.restype = ctypes.c_char_p
 _lib.iconv_status_string.argtypes = [_i]
 
+# symbols declared in include/iconv.h and include/iconv_bench.h
 EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
-           "iconv_probe_copy", "iconv_probe_mfma", "iconv_set_variant", "iconv_set_max_workgroups", "iconv_num_variants", "iconv_variant_name", "iconv_kernel_for",
-           "iconv_status_string"]
+           "iconv_kernel_for", "iconv_status_string"]
+EXPORTS_BENCH = ["iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy", "iconv_probe_mfma"]
 
 
 class IconvError(RuntimeError):
@@ -104,6 +105,18 @@ def iconv_fwd_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, st
 
 def iconv_fwd(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream=None) -> None:
     rc = iconv_fwd_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream)
+    if rc != 0:
+        raise IconvError(rc)
+
+
+def iconv_fwd_ex_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, variant=-1, max_workgroups=0, stream=None) -> int:
+    return _lib.iconv_fwd_ex(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride, pad, dilation, dtype,
+                             variant, max_workgroups, _stream(stream))
+
+
+def iconv_fwd_ex(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, variant=-1, max_workgroups=0, stream=None) -> None:
+    """iconv_fwd with a forced kernel-table entry and/or a cap on the workgroups, for this call only."""
+    rc = iconv_fwd_ex_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, variant, max_workgroups, stream)
     if rc != 0:
         raise IconvError(rc)
 
@@ -155,20 +168,12 @@ def iconv_probe_mfma(out, out_bytes, iters, random_operands=False, stream=None) 
         raise IconvError(rc)
 
 
-def iconv_set_variant(variant: int) -> None:
-    rc = _lib.iconv_set_variant(variant)
-    if rc != 0:
-        raise IconvError(rc)
-
-
-def iconv_set_max_workgroups(n: int) -> None:
-    rc = _lib.iconv_set_max_workgroups(n)
-    if rc != 0:
-        raise IconvError(rc)
-
-
 def iconv_num_variants() -> int:
     return _lib.iconv_num_variants()
+
+
+def iconv_variant_accepts(variant, N, H, W, C, K, R, S, stride, pad, dilation, dtype) -> bool:
+    return bool(_lib.iconv_variant_accepts(variant, N, H, W, C, K, R, S, stride, pad, dilation, dtype))
 
 
 def iconv_variant_name(variant: int) -> str:
@@ -206,7 +211,11 @@ def conv2d_nhwc(x, w, stride=1, pad=0, dilation=1, dtype=BF16_F32, explicit=Fals
     if explicit:
         nbytes = iconv_workspace_bytes(ALGO_EXPLICIT, N, H, W, C, K, R, S, stride, pad, dilation, dtype)
         ws = torch.empty(nbytes, dtype=torch.uint8, device=x.device)
+        if stream is not None and not isinstance(stream, int):
+            ws.record_stream(stream)        # the block must not be handed out again before the two kernels have run
         iconv_fwd_explicit(x, w, y, ws, nbytes, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream)
+        if isinstance(stream, int) and stream != torch.cuda.current_stream().cuda_stream:
+            torch.cuda.synchronize()        # a raw stream handle cannot be recorded: finish before ws is dropped
     else:
         iconv_fwd(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream)
     return y

@@ -1,13 +1,15 @@
 // C ABI of the library: argument checking, path selection, launches.  See include/iconv.h.
-#include <atomic>
-
+#include "iconv_bench.h"
 #include "iconv_common.h"
+#include "iconv_host.h"
 
 using namespace iconv;
 
 namespace {
 
-std::atomic<int> g_variant{-1};
+// Launch width asked for by the iconv_fwd_ex call that is running on this thread (0 = fill the
+// device).  Set and restored inside that one call, so no call sees another's value.
+thread_local int tl_max_workgroups = 0;
 
 int out_dim(int in, int filt, int stride, int pad, int dil) {
     long span = (long)in + 2L * pad - (long)dil * (filt - 1) - 1;
@@ -52,15 +54,47 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 int status_of(hipError_t e) { return e == hipSuccess ? ICONV_OK : ICONV_ERR_LAUNCH; }
 
-// Runs the convolution with the fastest kernel that accepts the shape.
-int run_conv(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t st) {
+// The launchers report hipGetLastError() after their launch; an error some earlier, unrelated HIP
+// call left on this thread must not be taken for theirs, so it is consumed first.
+void drop_stale_error() { (void)hipGetLastError(); }
+
+// Runs the convolution with the fastest kernel that accepts the shape (variant < 0), or with the
+// kernel-table entry `variant` where that entry can run it.
+int run_conv(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int variant, hipStream_t st) {
+    drop_stale_error();
     if (in_t != IN_F32 && (s.C % 8) == 0)
-        return status_of(launch_mfma(x, w, y, s, in_t, out_t, g_variant.load(), st));
+        return status_of(launch_mfma(x, w, y, s, in_t, out_t, variant, st));
     if (in_t != IN_F32 && stem_supported(s)) return status_of(launch_stem(x, w, y, s, in_t, out_t, st));
     return status_of(launch_direct(x, w, y, s, in_t, out_t, st));
 }
 
+// Shape, type and lowered-matrix size of the explicit variant.  Returns an ICONV_* status.
+int explicit_shape(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dil, int dtype, ConvShape* s,
+                   int* in_t, int* out_t, size_t* need) {
+    int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dil, s);
+    if (rc != ICONV_OK) return rc;
+    if (!dtype_types(dtype, in_t, out_t)) return ICONV_ERR_UNSUPPORTED;
+    if ((size_t)s->M * (size_t)s->Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
+    *need = (size_t)s->M * (size_t)s->Kg * (size_t)in_bytes(*in_t);
+    return ICONV_OK;
+}
+
+// Lowering kernel into `workspace`, then the GEMM: a 1x1 stride-1 convolution over the lowered
+// matrix seen as a 1 x 1 x M image with Kg channels; the KRSC filter tensor already is the
+// K x Kg filter matrix in the same (tap-row, tap-column, channel) column order.
+int run_explicit(const void* x, const void* w, void* y, void* workspace, const ConvShape& s, int in_t, int out_t,
+                 hipStream_t st) {
+    drop_stale_error();
+    if (launch_im2col(x, workspace, s, in_bytes(in_t), st) != hipSuccess) return ICONV_ERR_LAUNCH;
+    ConvShape g;
+    g.N = 1; g.H = 1; g.W = s.M; g.C = s.Kg; g.K = s.K; g.R = 1; g.S = 1;
+    g.stride = 1; g.pad = 0; g.dil = 1; g.P = 1; g.Q = s.M; g.PQ = s.M; g.M = s.M; g.Kg = s.Kg;
+    return run_conv(workspace, w, y, g, in_t, out_t, -1, st);
+}
+
 }  // namespace
+
+int iconv::call_max_workgroups() { return tl_max_workgroups; }
 
 extern "C" {
 
@@ -82,7 +116,24 @@ int iconv_fwd(const void* x, const void* w, void* y, int N, int H, int W, int C,
     int in_t, out_t;
     if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return ICONV_ERR_ALIGN;
-    return run_conv(x, w, y, s, in_t, out_t, (hipStream_t)stream);
+    return run_conv(x, w, y, s, in_t, out_t, -1, (hipStream_t)stream);
+}
+
+int iconv_fwd_ex(const void* x, const void* w, void* y, int N, int H, int W, int C, int K, int R, int S,
+                 int stride, int pad, int dilation, int dtype, int variant, int max_workgroups, void* stream) {
+    if (!x || !w || !y) return ICONV_ERR_NULL;
+    ConvShape s;
+    int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s);
+    if (rc != ICONV_OK) return rc;
+    int in_t, out_t;
+    if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
+    if (variant < -1 || variant >= mfma_num_variants() || max_workgroups < 0) return ICONV_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return ICONV_ERR_ALIGN;
+    const int saved = tl_max_workgroups;
+    tl_max_workgroups = max_workgroups;
+    rc = run_conv(x, w, y, s, in_t, out_t, variant, (hipStream_t)stream);
+    tl_max_workgroups = saved;
+    return rc;
 }
 
 int iconv_fwd_channel_last(const void* x_nchw, const void* w_kcrs, void* y, int N, int H, int W, int C, int K, int R, int S,
@@ -94,6 +145,7 @@ int iconv_fwd_channel_last(const void* x_nchw, const void* w_kcrs, void* y, int 
     int in_t, out_t;
     if (!dtype_types(dtype, &in_t, &out_t) || in_t == IN_F32) return ICONV_ERR_UNSUPPORTED;
     if (!aligned16(x_nchw) || !aligned16(w_kcrs) || !aligned16(y)) return ICONV_ERR_ALIGN;
+    drop_stale_error();
     return status_of(launch_channel_last(x_nchw, w_kcrs, y, s, in_t, out_t, (hipStream_t)stream));
 }
 
@@ -119,6 +171,7 @@ int iconv_im2col(const void* x, void* workspace, size_t workspace_bytes, int N, 
     if ((size_t)s.M * (size_t)s.Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < need) return ICONV_ERR_WORKSPACE;
     if (!aligned16(x) || !aligned16(workspace)) return ICONV_ERR_ALIGN;
+    drop_stale_error();
     return status_of(launch_im2col(x, workspace, s, in_bytes(in_t), (hipStream_t)stream));
 }
 
@@ -127,30 +180,20 @@ int iconv_fwd_explicit(const void* x, const void* w, void* y, void* workspace, s
                        void* stream) {
     if (!x || !w || !y) return ICONV_ERR_NULL;
     ConvShape s;
-    int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s);
-    if (rc != ICONV_OK) return rc;
     int in_t, out_t;
-    if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
-    if ((size_t)s.M * (size_t)s.Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
-    const size_t need = (size_t)s.M * (size_t)s.Kg * (size_t)in_bytes(in_t);
+    size_t need = 0;
+    int rc = explicit_shape(N, H, W, C, K, R, S, stride, pad, dilation, dtype, &s, &in_t, &out_t, &need);
+    if (rc != ICONV_OK) return rc;
     if (!workspace || workspace_bytes < need) return ICONV_ERR_WORKSPACE;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(workspace)) return ICONV_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)stream;
-    hipError_t e = launch_im2col(x, workspace, s, in_bytes(in_t), st);
-    if (e != hipSuccess) return ICONV_ERR_LAUNCH;
-    // The GEMM is a 1x1 stride-1 convolution over the lowered matrix seen as a 1 x 1 x M image
-    // with Kg channels; the KRSC filter tensor already is the K x Kg filter matrix in the same
-    // (tap-row, tap-column, channel) column order.
-    ConvShape g;
-    g.N = 1; g.H = 1; g.W = s.M; g.C = s.Kg; g.K = s.K; g.R = 1; g.S = 1;
-    g.stride = 1; g.pad = 0; g.dil = 1; g.P = 1; g.Q = s.M; g.PQ = s.M; g.M = s.M; g.Kg = s.Kg;
-    return run_conv(workspace, w, y, g, in_t, out_t, st);
+    return run_explicit(x, w, y, workspace, s, in_t, out_t, (hipStream_t)stream);
 }
 
 int iconv_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (!dst || !src) return ICONV_ERR_NULL;
     if (bytes == 0 || (bytes & 15u)) return ICONV_ERR_SHAPE;
     if (!aligned16(dst) || !aligned16(src)) return ICONV_ERR_ALIGN;
+    drop_stale_error();
     return status_of(launch_copy(dst, src, bytes, (hipStream_t)stream));
 }
 
@@ -159,6 +202,7 @@ int iconv_probe_mfma(void* out, size_t out_bytes, int iters, int random_operands
     if (iters < 1) return ICONV_ERR_SHAPE;
     if (out_bytes < (size_t)kMfmaProbeGroups * 256 * sizeof(float)) return ICONV_ERR_WORKSPACE;
     if (!aligned16(out)) return ICONV_ERR_ALIGN;
+    drop_stale_error();
     return status_of(launch_mfma_probe(out, iters, random_operands != 0, (hipStream_t)stream));
 }
 
@@ -173,19 +217,16 @@ const char* iconv_kernel_for(int N, int H, int W, int C, int K, int R, int S, in
     return "direct";
 }
 
-int iconv_set_variant(int variant) {
-    if (variant < -1 || variant >= mfma_num_variants()) return ICONV_ERR_UNSUPPORTED;
-    g_variant.store(variant);
-    return ICONV_OK;
-}
-
-int iconv_set_max_workgroups(int n) {
-    if (n < 0) return ICONV_ERR_UNSUPPORTED;
-    patch_set_max_workgroups(n);
-    return ICONV_OK;
-}
-
 int iconv_num_variants(void) { return mfma_num_variants(); }
+
+int iconv_variant_accepts(int variant, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dilation,
+                          int dtype) {
+    int in_t, out_t;
+    ConvShape s;
+    if (!dtype_types(dtype, &in_t, &out_t) || in_t == IN_F32) return 0;
+    if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK || (s.C % 8) != 0) return 0;
+    return mfma_variant_accepts(s, variant) ? 1 : 0;
+}
 
 const char* iconv_variant_name(int variant) {
     if (variant < 0 || variant >= mfma_num_variants()) return "auto";

@@ -58,14 +58,16 @@ hipError_t launch_direct(const void* x, const void* w, void* y, const ConvShape&
 
 int mfma_num_variants();
 const char* mfma_variant_name(int v);
+bool mfma_variant_accepts(const ConvShape& s, int v);   // entry v runs the layer itself (C % 8 == 0 assumed)
 int mfma_default_variant(const ConvShape& s);   // kernel-table entry chosen without an override (C % 8 == 0 layers)
 // Picks a tile variant (or uses `variant` when >= 0) and launches the implicit-GEMM kernel.
 // Requires C % 8 == 0 and a 16-bit input type.
 hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
                        int variant, hipStream_t stream);
 
-// Patch-reuse kernels (channel chunk outer, tap inner; input patch resident in LDS).
-void patch_set_max_workgroups(int n);   // 0 = one range of tiles per resident workgroup (default)
+// Patch-reuse kernels (channel chunk outer, tap inner; input patch resident in LDS).  Table order:
+enum PatchVariant { kP128x64, kP256x128, kP256x64, kP64x64, kP64x128, kP128x64Staged, kP256x128Pf, kP64x128Pf, kP64x128C128,
+                    kNumPatch };
 int patch_num_variants();
 const char* patch_variant_name(int v);
 bool patch_supported(const ConvShape& s, int v);

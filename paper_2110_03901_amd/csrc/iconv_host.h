@@ -50,7 +50,8 @@ inline int cached_occupancy(std::atomic<long long>& slot, const void* kern, int 
     return nb;
 }
 
-// Cap on the number of workgroups of a persistent launch (0 = none); see iconv_set_max_workgroups.
-extern std::atomic<int> g_max_workgroups;
+// Cap on the number of workgroups of a persistent launch asked for by the call that is running on
+// this thread (0 = none; only iconv_fwd_ex sets one, for its own duration).
+int call_max_workgroups();
 
 }  // namespace iconv

@@ -323,21 +323,21 @@ hipError_t launch_dma(const void* x, const void* w, void* y, const ConvShape& s,
 
 // Kernel table of this file (per-tap loader, direct-to-LDS, ST stages).  Name: BMxBNxBK, wave
 // tile, stages.
-#define ICONV_VARIANTS(X)                                                         \
-    X(0, "d128x128x32_w64x64_s3", (launch_dma<T, TO, 128, 128, 32, 64, 64, 3>))   \
-    X(1, "d128x128x64_w64x64_s3", (launch_dma<T, TO, 128, 128, 64, 64, 64, 3>))   \
-    X(2, "d128x64x64_w64x32_s4", (launch_dma<T, TO, 128, 64, 64, 64, 32, 4>))     \
-    X(3, "d256x128x64_w64x64_s3", (launch_dma<T, TO, 256, 128, 64, 64, 64, 3>))   \
-    X(4, "d256x256x32_w128x64_s3", (launch_dma<T, TO, 256, 256, 32, 128, 64, 3>)) \
-    X(5, "d64x64x64_w32x32_s4", (launch_dma<T, TO, 64, 64, 64, 32, 32, 4>))       \
-    X(6, "d128x128x64_w64x32_s3", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3>))   \
-    X(7, "d64x128x64_w32x64_s4", (launch_dma<T, TO, 64, 128, 64, 32, 64, 4>))        \
-    X(8, "d128x128x64_w64x32_s3_pf", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3, 1>))
+#define ICONV_VARIANTS(X)                                                                \
+    X(kD128x64, "d128x64x64_w64x32_s4", (launch_dma<T, TO, 128, 64, 64, 64, 32, 4>))          \
+    X(kD256x128, "d256x128x64_w64x64_s3", (launch_dma<T, TO, 256, 128, 64, 64, 64, 3>))       \
+    X(kD256x256, "d256x256x32_w128x64_s3", (launch_dma<T, TO, 256, 256, 32, 128, 64, 3>))     \
+    X(kD64x64, "d64x64x64_w32x32_s4", (launch_dma<T, TO, 64, 64, 64, 32, 32, 4>))             \
+    X(kD128x128, "d128x128x64_w64x32_s3", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3>))       \
+    X(kD128x128Pf, "d128x128x64_w64x32_s3_pf", (launch_dma<T, TO, 128, 128, 64, 64, 32, 3, 1>))
 
+#define X_ENUM(i, name, fn) i,
+enum DmaVariant { ICONV_VARIANTS(X_ENUM) kNumVariants };
+#undef X_ENUM
 #define X_NAME(i, name, fn) name,
 const char* const kVariantNames[] = {ICONV_VARIANTS(X_NAME)};
 #undef X_NAME
-constexpr int kNumVariants = sizeof(kVariantNames) / sizeof(kVariantNames[0]);
+static_assert(sizeof(kVariantNames) / sizeof(kVariantNames[0]) == kNumVariants, "one name per kernel");
 
 template <typename T, typename TO>
 hipError_t launch_variant(int v, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
@@ -368,28 +368,28 @@ int choose_variant(const ConvShape& s) {
         int v;
         const long tiles_256x64 = (long)((s.M + 255) / 256) * ((s.K + 63) / 64);
         if (s.K <= 64)                                // p256x64 (eight compute waves of 32x64), p128x64 or p64x64
-            v = (s.M + 255) / 256 >= 128 ? P0 + 5 : (s.M + 127) / 128 >= 128 ? P0 + 1 : P0 + 7;
+            v = (s.M + 255) / 256 >= 128 ? kP256x64 : (s.M + 127) / 128 >= 128 ? kP128x64 : kP64x64;
         else if (tiles_256x128 >= 190)                // p256x128; with many channel chunks per tap, operands prefetched
-            v = s.C >= 256 ? P0 + 17 : P0 + 3;        // one group of K slices ahead
-        else if (tiles_256x64 >= 190) v = P0 + 5;     // p256x64 when that still gives most compute units a tile
-        else if (s.C % 128 == 0) v = P0 + 20;         // p64x128 (many small tiles), 128-channel chunks: half the steps
-        else v = P0 + 19;                             // p64x128, prefetching
-        if (patch_supported(s, v - P0)) return v;
-        if (v != P0 + 8 && s.K > 64 && patch_supported(s, 8)) return P0 + 8;
+            v = s.C >= 256 ? kP256x128Pf : kP256x128; // one group of K slices ahead
+        else if (tiles_256x64 >= 190) v = kP256x64;   // p256x64 when that still gives most compute units a tile
+        else if (s.C % 128 == 0) v = kP64x128C128;    // p64x128 (many small tiles), 128-channel chunks: half the steps
+        else v = kP64x128Pf;                          // p64x128, prefetching
+        if (patch_supported(s, v)) return P0 + v;
+        if (v != kP64x128 && s.K > 64 && patch_supported(s, kP64x128)) return P0 + kP64x128;
     }
     if (s.R * s.S == 1) {
         const long tiles_256x256 = (long)((s.M + 255) / 256) * ((s.K + 255) / 256);
-        if (s.K > 128 && tiles_256x256 >= 160) return 4;   // d256x256x32
-        if (tiles_256x128 >= 160) return 3;                // d256x128x64
-        if (s.K <= 64) return 2;                           // d128x64x64
-        return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 160 ? 6 : 5;    // d128x128x64, else d64x64x64
+        if (s.K > 128 && tiles_256x256 >= 160) return kD256x256;
+        if (tiles_256x128 >= 160) return kD256x128;
+        if (s.K <= 64) return kD128x64;
+        return (long)((s.M + 127) / 128) * ((s.K + 127) / 128) >= 160 ? kD128x128 : kD64x64;
     }
-    if (s.K <= 64) return 2;                          // d128x64x64
+    if (s.K <= 64) return kD128x64;
     const long tiles_128x128 = (long)((s.M + 127) / 128) * ((s.K + 127) / 128);
     // d128x128x64 (operands prefetched a step ahead) while its tiles fit one round of workgroups; d256x128x64 when
     // they do not and the larger tiles still reach half the compute units; d64x64x64 for very small outputs
-    if (tiles_128x128 > device_cus() && tiles_256x128 >= device_cus() / 2) return 3;
-    return tiles_128x128 >= 128 ? 8 : 5;
+    if (tiles_128x128 > device_cus() && tiles_256x128 >= device_cus() / 2) return kD256x128;
+    return tiles_128x128 >= 128 ? kD128x128Pf : kD64x64;
 }
 
 }  // namespace
@@ -404,6 +404,14 @@ const char* mfma_variant_name(int v) {
 }
 
 int mfma_default_variant(const ConvShape& s) { return choose_variant(s); }
+
+bool mfma_variant_accepts(const ConvShape& s, int v) {
+    const int R0 = kNumVariants + patch_num_variants();
+    if (v < 0 || v >= mfma_num_variants()) return false;
+    if (v >= R0) return resident_supported(s, v - R0);
+    if (v >= kNumVariants) return patch_supported(s, v - kNumVariants);
+    return true;
+}
 
 hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int variant,
                        hipStream_t st) {

@@ -735,7 +735,7 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
     const int occ = cached_occupancy(occ_slot, (const void*)kern, c.waves() * 64, lds_bytes);
     int nwg = 1;
     g.total_tiles = (int)total;
-    const int cap = g_max_workgroups.load(std::memory_order_relaxed);
+    const int cap = call_max_workgroups();
     if (cap > 0) {
         split_tiles(total, cap, 1, &g.tiles_per_wg, &nwg);
     } else {
@@ -748,34 +748,21 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
 //   name                                  CB  WM WN MI NI STB LA NLD SS NSW PF
 // (compute + loader [+ store] waves; SS > 0: output staged in LDS and drained by NSW store waves;
 //  PF: operands of the next group of K slices are read before the current group's MFMAs)
-#define ICONV_PATCH_VARIANTS(X)                                                   \
-    X(0, "p256x64_c64_w64x64_s3_4+4", 64, 4, 1, 2, 2, 3, 2, 4, 0, 0, 0)           \
-    X(1, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 0)           \
-    X(2, "p128x128_c64_w64x64_s3_4+4", 64, 2, 2, 2, 2, 3, 2, 4, 0, 0, 0)          \
-    X(3, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 0)          \
-    X(4, "p128x128_c32_w64x64_s4_4+4", 32, 2, 2, 2, 2, 4, 2, 4, 0, 0, 0)          \
-    X(5, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 0)           \
-    X(6, "p256x64_c64_w64x32_s3_8+4", 64, 4, 2, 2, 1, 3, 2, 4, 0, 0, 0)           \
-    X(7, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 0)            \
-    X(8, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)           \
-    X(9, "p128x256_c32_w64x64_s3_8+4", 32, 2, 4, 2, 2, 3, 1, 4, 0, 0, 0)          \
-    X(10, "p256x128_c64_w128x64_s3_4+4", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 0)        \
-    X(11, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 0)        \
-    X(12, "p256x64_c64_w32x64_s3_8+4+2", 64, 8, 1, 1, 2, 3, 2, 4, 4, 2, 0)        \
-    X(13, "p256x64_c64_w64x64_s3_4+4+2", 64, 4, 1, 2, 2, 3, 2, 4, 4, 2, 0)        \
-    X(14, "p64x64_c64_w32x32_s3_4+4+2", 64, 2, 2, 1, 1, 3, 1, 4, 1, 2, 0)         \
-    X(15, "p128x128_c64_w64x64_s3_4+4+2", 64, 2, 2, 2, 2, 3, 2, 4, 2, 2, 0)       \
-    X(16, "p64x128_c64_w32x64_s3_4+4+2", 64, 2, 2, 1, 2, 3, 1, 4, 1, 2, 0)        \
-    X(17, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1)      \
-    X(18, "p256x128_c64_w128x64_s3_4+4_pf", 64, 2, 2, 4, 2, 3, 3, 4, 0, 0, 1)     \
-    X(19, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1)       \
-    X(20, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)        \
-    X(21, "p64x128_c128_w32x64_s3_4+4_pf", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 1)
+#define ICONV_PATCH_VARIANTS(X)                                                              \
+    X(kP128x64, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 0)                \
+    X(kP256x128, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 0)              \
+    X(kP256x64, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 0)                \
+    X(kP64x64, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 0)                  \
+    X(kP64x128, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)                \
+    X(kP128x64Staged, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 0)        \
+    X(kP256x128Pf, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1)         \
+    X(kP64x128Pf, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1)           \
+    X(kP64x128C128, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)
 
 #define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf},
 const PatchCfg kPatchCfgs[] = {ICONV_PATCH_VARIANTS(X_CFG)};
 #undef X_CFG
-constexpr int kNumPatch = sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]);
+static_assert(sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]) == kNumPatch, "one configuration per kernel");
 
 template <typename T, typename TO>
 hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
@@ -790,8 +777,6 @@ hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const Co
 
 }  // namespace
 
-std::atomic<int> g_max_workgroups{0};
-void patch_set_max_workgroups(int n) { g_max_workgroups.store(n < 0 ? 0 : n); }
 int patch_num_variants() { return kNumPatch; }
 const char* patch_variant_name(int v) { return kPatchCfgs[v].name; }
 

@@ -400,7 +400,7 @@ hipError_t launch_res_t(const void* x, const void* w, void* y, const ConvShape& 
     }
     static std::atomic<long long> occ_slot{-1};
     const int occ = cached_occupancy(occ_slot, (const void*)kern, threads, lds_bytes);
-    const int cap = g_max_workgroups.load(std::memory_order_relaxed);
+    const int cap = call_max_workgroups();
     const long slots = cap > 0 ? cap : (long)device_cus() * occ;
     const long per = (g.total_tiles + slots - 1) / slots;
     const int nwg = (int)((g.total_tiles + per - 1) / per);

@@ -397,7 +397,7 @@ hipError_t launch_stem_t(const void* x, const void* w, void* y, const ConvShape&
         const int occ = cached_occupancy(occ_slot, (const void*)kern, threads, lds_bytes);
         // The kernel waits on memory most of the time, so every workgroup slot of the device is
         // filled (as many resident workgroups per compute unit as fit), each with an equal range.
-        const int cap = g_max_workgroups.load(std::memory_order_relaxed);
+        const int cap = call_max_workgroups();
         const long slots = cap > 0 ? cap : (long)device_cus() * occ;
         const long per = (g.total_tiles + slots - 1) / slots;
         nwg = (int)((g.total_tiles + per - 1) / per);

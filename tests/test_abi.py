@@ -1,6 +1,7 @@
-"""CPU-side checks of the boundary: the library loads, exports every symbol the header
-declares, and its host-only entry points (shape, workspace size, status strings, argument
-validation that returns before any launch) behave as include/iconv.h states."""
+"""CPU-side checks of the boundary: the library loads, exports every symbol the two headers
+declare (include/iconv.h: the convolution contract; include/iconv_bench.h: test and measurement
+entry points), and its host-only entry points (shape, workspace size, status strings, argument
+validation that returns before any launch) behave as the headers state."""
 import ctypes
 import os
 import re
@@ -10,6 +11,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2110_03901_amd", "libiconv_mi355.so")
 HEADER = os.path.join(ROOT, "include", "iconv.h")
+HEADER_BENCH = os.path.join(ROOT, "include", "iconv_bench.h")
 
 
 @pytest.fixture(scope="module")
@@ -20,16 +22,30 @@ def lib():
     return ctypes.CDLL(LIB)
 
 
-def declared_functions():
-    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+def declared_functions(header):
+    text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
     return sorted(set(re.findall(r"\b(iconv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_exported(lib):
-    names = declared_functions()
-    assert "iconv_fwd" in names and "iconv_fwd_explicit" in names and len(names) >= 9
-    for n in names:
-        assert hasattr(lib, n), f"{n} declared in iconv.h but not exported"
+    names = declared_functions(HEADER)
+    assert {"iconv_fwd", "iconv_out_shape", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_status_string"} <= set(names)
+    bench = declared_functions(HEADER_BENCH)
+    assert {"iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy",
+            "iconv_probe_mfma"} == set(bench)
+    for n in names + bench:
+        assert hasattr(lib, n), f"{n} is declared in a header but not exported"
+
+
+def test_contract_header_declares_no_switches():
+    """iconv.h is the convolution contract: no process-wide override and no measurement helper is
+    declared there, and the binding lists the same symbols as the headers."""
+    names = set(declared_functions(HEADER))
+    assert not any(n.startswith(("iconv_set_", "iconv_probe_")) for n in names)
+    src = open(os.path.join(ROOT, "paper_2110_03901_amd", "binding.py")).read()
+    listed = set(re.findall(r'"(iconv_[a-z0-9_]+)"', src.split("EXPORTS =")[1].split("\n\n")[0]))
+    assert "iconv_fwd_ex" in listed
+    assert listed == names | set(declared_functions(HEADER_BENCH))
 
 
 def test_out_shape(lib):
@@ -82,7 +98,21 @@ def test_status_strings_and_variants(lib):
     lib.iconv_variant_name.restype = ctypes.c_char_p
     n = lib.iconv_num_variants()
     assert n >= 1 and len({lib.iconv_variant_name(i) for i in range(n)}) == n
-    assert lib.iconv_set_variant(n) == -3 and lib.iconv_set_variant(-1) == 0
+    assert lib.iconv_variant_name(n) == b"auto" and lib.iconv_variant_name(-1) == b"auto"
+
+
+def test_extended_call_validates_its_overrides(lib):
+    f = lib.iconv_fwd_ex
+    f.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 13 + [ctypes.c_void_p]
+    ok = (1, 8, 8, 16, 16, 3, 3, 1, 1, 1)
+    a = 4096  # fake aligned address, never dereferenced on these paths
+    n = lib.iconv_num_variants()
+    assert f(a, a, a, *ok, 1, n, 0, None) == -3          # no such kernel-table entry
+    assert f(a, a, a, *ok, 1, -2, 0, None) == -3
+    assert f(a, a, a, *ok, 1, -1, -1, None) == -3        # negative workgroup cap
+    assert f(None, a, a, *ok, 1, -1, 0, None) == -1
+    assert f(a, a, a, 1, 2, 2, 16, 16, 3, 3, 1, 0, 1, 1, -1, 0, None) == -2
+    assert f(a + 4, a, a, *ok, 1, 0, 0, None) == -4
 
 
 def kernel_for(lib, *args):

@@ -19,7 +19,6 @@ def B():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from paper_2110_03901_amd import binding
-    binding.iconv_set_variant(-1)
     return binding
 
 
@@ -31,7 +30,9 @@ def code_of(L, out16=False):
     return 4 if out16 else 2
 
 
-def run_gpu(B, L, x, w, code, explicit=False):
+def run_gpu(B, L, x, w, code, explicit=False, variant=-1, cap=0):
+    """One call through the C ABI.  variant / cap: a forced kernel-table entry / a cap on the
+    workgroups of the persistent kernels, for this call only (iconv_fwd_ex)."""
     xd, wd = B.to_device(x, code), B.to_device(w, code)
     y = B.empty_output(L.N, L.P, L.Q, L.K, code)
     y.fill_(float("nan"))                      # every element must be overwritten
@@ -39,6 +40,8 @@ def run_gpu(B, L, x, w, code, explicit=False):
         nbytes = B.iconv_workspace_bytes(B.ALGO_EXPLICIT, *L.shape_args(), code)
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
         B.iconv_fwd_explicit(xd, wd, y, ws, nbytes, *L.shape_args(), code)
+    elif variant >= 0 or cap > 0:
+        B.iconv_fwd_ex(xd, wd, y, *L.shape_args(), code, variant, cap)
     else:
         B.iconv_fwd(xd, wd, y, *L.shape_args(), code)
     torch.cuda.synchronize()
@@ -51,10 +54,14 @@ def rel_err(got, ref):
     return np.abs(got - ref).max() / np.abs(ref).max()
 
 
-def check(B, L, explicit=False, seed_offset=0):
+def variant_names(B):
+    return [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
+
+
+def check(B, L, explicit=False, seed_offset=0, variant=-1, cap=0):
     x, w = workloads.make_inputs(L, seed_offset)
     ref = conv_ref(x, w, L.stride, L.pad, L.dilation)
-    got = run_gpu(B, L, x, w, code_of(L), explicit)
+    got = run_gpu(B, L, x, w, code_of(L), explicit, variant, cap)
     err = rel_err(got, ref)
     print(f"{L.name}: M={L.M} K={L.K} Kg={L.k_gemm} rel_err={err:.3e}", flush=True)
     assert err <= BAR
@@ -138,14 +145,10 @@ def test_every_tile_variant(B):
               workloads.small_layer("v_c", 2, 14, 15, 136, 72, 3, 3, 1, 1, 1, seed_id=812),   # 3 channel chunks
               workloads.small_layer("v_d", 1, 70, 9, 128, 40, 5, 5, 1, 2, 1, seed_id=813),    # tall, 25 taps
               workloads.small_layer("v_e", 3, 9, 9, 192, 64, 1, 1, 1, 0, 1, seed_id=814)]     # 1x1
-    try:
-        for v in range(B.iconv_num_variants()):
-            B.iconv_set_variant(v)
-            for L in shapes:
-                print("variant", B.iconv_variant_name(v), flush=True)
-                check(B, L)
-    finally:
-        B.iconv_set_variant(-1)
+    for v, nm in enumerate(variant_names(B)):
+        for L in shapes:
+            print("variant", nm, flush=True)
+            check(B, L, variant=v)
 
 
 def test_workgroups_walking_several_tiles(B):
@@ -155,19 +158,12 @@ def test_workgroups_walking_several_tiles(B):
     shapes = [workloads.small_layer("w_a", 3, 20, 22, 64, 136, 3, 3, 1, 1, 1, seed_id=815),    # one chunk, 2 N tiles
               workloads.small_layer("w_b", 2, 17, 19, 136, 72, 3, 3, 1, 1, 1, seed_id=816),    # three chunks
               workloads.small_layer("w_c", 2, 24, 24, 72, 64, 5, 5, 1, 4, 2, seed_id=817)]     # dilated, ragged chunk
-    try:
-        for cap in (1, 2, 5):
-            B.iconv_set_max_workgroups(cap)
-            for v in [-1] + list(range(B.iconv_num_variants())):
-                if "p" != B.iconv_variant_name(v)[0] and v >= 0:
-                    continue
-                B.iconv_set_variant(v)
-                for L in shapes:
-                    print("cap", cap, "variant", B.iconv_variant_name(v), flush=True)
-                    check(B, L)
-    finally:
-        B.iconv_set_variant(-1)
-        B.iconv_set_max_workgroups(0)
+    names = variant_names(B)
+    for cap in (1, 2, 5):
+        for v in [-1] + [i for i, nm in enumerate(names) if nm.startswith("p")]:
+            for L in shapes:
+                print("cap", cap, "variant", B.iconv_variant_name(v), flush=True)
+                check(B, L, variant=v, cap=cap)
 
 
 def test_resident_filter_kernels(B):
@@ -181,20 +177,14 @@ def test_resident_filter_kernels(B):
               workloads.small_layer("r_d", 1, 33, 31, 64, 48, 3, 3, 2, 1, 1, seed_id=843),     # stride 2
               workloads.small_layer("r_e", 2, 30, 9, 128, 64, 1, 3, 1, 1, 1, dtype="f16", seed_id=844),   # 1x3, four slices
               workloads.small_layer("r_f", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1, seed_id=845)]     # full-width blocks of 7 rows
-    names = [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
+    names = variant_names(B)
     res = [v for v, nm in enumerate(names) if nm.startswith("r")]
-    assert len(res) == 2
-    try:
-        for cap in (0, 1, 3):
-            B.iconv_set_max_workgroups(cap)
-            for v in res:
-                B.iconv_set_variant(v)
-                for L in shapes:
-                    print("cap", cap, "variant", names[v], L.name, flush=True)
-                    check(B, L)
-    finally:
-        B.iconv_set_variant(-1)
-        B.iconv_set_max_workgroups(0)
+    assert len(res) >= 2
+    for cap in (0, 1, 3):
+        for v in res:
+            for L in shapes:
+                print("cap", cap, "variant", names[v], L.name, flush=True)
+                check(B, L, variant=v, cap=cap)
 
 
 def test_merged_tap_workgroups_walking_several_blocks(B):
@@ -205,14 +195,10 @@ def test_merged_tap_workgroups_walking_several_blocks(B):
               workloads.small_layer("m_b", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1, seed_id=831),    # 32-wide blocks, even pad
               workloads.small_layer("m_c", 5, 24, 40, 4, 24, 3, 3, 2, 1, 1, dtype="f16", seed_id=832),
               workloads.small_layer("m_d", 2, 30, 36, 4, 64, 7, 7, 2, 3, 1, seed_id=833)]
-    try:
-        for cap in (0, 1, 2, 3):
-            B.iconv_set_max_workgroups(cap)
-            for L in shapes:
-                print("cap", cap, L.name, flush=True)
-                check(B, L)
-    finally:
-        B.iconv_set_max_workgroups(0)
+    for cap in (0, 1, 2, 3):
+        for L in shapes:
+            print("cap", cap, L.name, flush=True)
+            check(B, L, cap=cap)
 
 
 def test_staged_output_repeated_runs(B):
@@ -228,37 +214,94 @@ def test_staged_output_repeated_runs(B):
     for L in shapes:
         x, w = workloads.make_inputs(L)
         prepared.append((L, x, w, conv_ref(x, w, L.stride, L.pad, L.dilation)))
-    try:
-        for v in staged:
-            B.iconv_set_variant(v)
-            for cap in (0, 3):
-                B.iconv_set_max_workgroups(cap)
-                for L, x, w, ref in prepared:
-                    for rep in range(6):
-                        err = rel_err(run_gpu(B, L, x, w, code_of(L)), ref)
-                        assert err <= TIGHT, (B.iconv_variant_name(v), cap, L.name, rep, err)
-            print("staged variant", B.iconv_variant_name(v), "ok", flush=True)
-    finally:
-        B.iconv_set_variant(-1)
-        B.iconv_set_max_workgroups(0)
+    for v in staged:
+        for cap in (0, 3):
+            for L, x, w, ref in prepared:
+                for rep in range(6):
+                    err = rel_err(run_gpu(B, L, x, w, code_of(L), variant=v, cap=cap), ref)
+                    assert err <= TIGHT, (B.iconv_variant_name(v), cap, L.name, rep, err)
+        print("staged variant", B.iconv_variant_name(v), "ok", flush=True)
 
 
 # ---- 16-bit outputs: correctly rounded accumulators ------------------------------------------
 
+def check_sixteen_bit(B, L, variant=-1, cap=0, seed_offset=0):
+    """bf16 / fp16 output against the oracle: every element within one ulp of the output type (plus the
+    fp32 accumulation error), and equal to the oracle rounded onto the type's grid almost everywhere
+    (they differ only where the fp32 sum and the fp64 sum fall on different sides of a rounding boundary)."""
+    x, w = workloads.make_inputs(L, seed_offset)
+    ref = conv_ref(x, w, L.stride, L.pad, L.dilation)
+    got = run_gpu(B, L, x, w, code_of(L, out16=True), variant=variant, cap=cap)
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    mant = 7 if L.dtype == "bf16" else 10
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -14))) - mant)
+    # 4e-6: fp32 accumulation of at most 4608 products of magnitude < 1/sqrt(K_gemm)
+    worst = float((np.abs(got - ref) - ulp).max())
+    same = float((got == workloads.round_to_grid(ref.astype(np.float32), L.dtype)).mean())
+    print(f"{L.name} {L.dtype} out: worst excess over one ulp {worst:.2e}, equal to the rounded oracle {same:.4f}", flush=True)
+    assert worst <= 4e-6
+    assert same > 0.99
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 def test_sixteen_bit_output_within_one_ulp(B, dtype):
-    L = workloads.small_layer("out16", 2, 14, 14, 64, 64, 3, 3, 1, 1, 1, dtype=dtype, seed_id=820)
-    x, w = workloads.make_inputs(L)
-    ref = conv_ref(x, w, L.stride, L.pad, L.dilation)
-    got = run_gpu(B, L, x, w, code_of(L, out16=True))
-    # ulp of the 16-bit type at |ref|: 2^(floor(log2|ref|) - mantissa_bits)
-    mant = 7 if dtype == "bf16" else 10
-    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -14))) - mant)
-    # one ulp of the output type plus the fp32 accumulation error of a 576-term sum of |terms| < 1
-    assert (np.abs(got - ref) <= ulp + 4e-6).all()
-    # and rounding the oracle to the type reproduces almost every element exactly
-    same = got == workloads.round_to_grid(ref.astype(np.float32), dtype)
-    assert same.mean() > 0.99
+    check_sixteen_bit(B, workloads.small_layer("out16", 2, 14, 14, 64, 64, 3, 3, 1, 1, 1, dtype=dtype, seed_id=820))
+
+
+# (case name, kernel-table entry forced ("" = the library's choice), workgroup cap, layer): one per epilogue that
+# converts to a 16-bit type -- resident-filter (staged, 7 and 8 fragments), per-tap with staged whole-line stores
+# (K % 4 == 0) and with the direct / scalar-tail stores (K % 4 != 0), per-tap prefetching, patch-reuse direct
+# (several tiles per workgroup) and last-tile staged, patch-reuse drained by store waves, prefetching patch-reuse,
+# merged-tap stem, plain direct kernel.
+OUT16_CASES = [
+    ("res_f7", "r448x64", 0, ("o_r7", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1)),
+    ("res_f7_walk", "r448x64", 3, ("o_r7w", 3, 28, 28, 64, 48, 3, 3, 1, 1, 1)),
+    ("res_f8_1x1", "r512x64", 0, ("o_r8", 2, 32, 32, 96, 64, 1, 1, 1, 0, 1)),
+    ("tap_256x256x32_staged", "d256x256x32", 0, ("o_t4", 2, 28, 28, 72, 264, 1, 1, 2, 0, 1)),
+    ("tap_128x128_pf_staged", "d128x128x64_w64x32_s3_pf", 0, ("o_t8", 2, 30, 30, 128, 160, 3, 3, 2, 1, 1)),
+    ("tap_128x64_scalar_tail", "d128x64x64", 0, ("o_t2", 2, 15, 17, 32, 42, 3, 3, 2, 1, 1)),
+    ("tap_64x64_k_odd", "d64x64x64", 0, ("o_t5", 1, 12, 12, 72, 37, 3, 3, 1, 1, 1)),
+    ("tap_256x128", "d256x128x64", 0, ("o_t3", 3, 20, 20, 64, 136, 1, 1, 1, 0, 1)),
+    ("patch_direct_walk", "p128x64_c64_w32x64_s3_4+4", 2, ("o_p1", 3, 20, 22, 64, 72, 3, 3, 1, 1, 1)),
+    ("patch_256x128", "p256x128_c64_w64x64_s3_8+4", 0, ("o_p3", 2, 24, 24, 64, 136, 3, 3, 1, 2, 2)),
+    ("patch_store_waves", "p128x64_c64_w32x64_s3_4+4+2", 3, ("o_p11", 4, 28, 28, 64, 64, 3, 3, 1, 1, 1)),
+    ("patch_pf", "p256x128_c64_w64x64_s3_8+4_pf", 1, ("o_p17", 2, 20, 22, 136, 200, 3, 3, 1, 1, 1)),
+    ("patch_pf_small_tiles", "p64x128_c64_w32x64_s4_4+4_pf", 0, ("o_p19", 5, 7, 7, 136, 160, 3, 3, 1, 1, 1)),
+    ("patch_c128", "p64x128_c128", 2, ("o_p20", 6, 7, 7, 256, 128, 3, 3, 1, 1, 1)),
+    ("patch_k_odd", "p64x64", 0, ("o_p7", 2, 14, 15, 40, 37, 3, 3, 1, 1, 1)),
+    ("stem", "", 0, ("o_stem", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1)),
+    ("stem_walk_k40", "", 2, ("o_stem2", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1)),
+    ("direct_c3", "", 0, ("o_d3", 2, 9, 10, 3, 5, 3, 3, 1, 1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", OUT16_CASES, ids=[c[0] for c in OUT16_CASES])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_sixteen_bit_output_through_every_epilogue(B, case, dtype):
+    label, forced, cap, (name, *dims) = case
+    L = workloads.small_layer(name, *dims, dtype=dtype, seed_id=950 + len(label))
+    v = -1
+    if forced:
+        hits = [i for i, nm in enumerate(variant_names(B)) if nm.startswith(forced)]
+        assert hits, f"no kernel-table entry starts with {forced}"
+        v = hits[0]
+        assert B.iconv_variant_accepts(v, *L.shape_args(), code_of(L, out16=True)), f"{forced} does not take {dims}"
+    elif L.C % 8 == 0:
+        pytest.fail("cases without a forced entry are meant for the stem and direct kernels")
+    check_sixteen_bit(B, L, variant=v, cap=cap)
+
+
+@pytest.mark.parametrize("name,batch", [("cfg2", 32), ("cfg3a", 8), ("cfg3b", 8), ("cfg4", 2), ("cfg5a", 4), ("cfg5b", 64)])
+def test_sixteen_bit_output_benchmark_layers(B, name, batch):
+    """The benchmark layers with bf16 output through the library's own kernel choice (cfg2 and cfg5b at full size)."""
+    L = workloads.LAYERS[name]
+    check_sixteen_bit(B, L if batch == L.N else workloads.with_batch(L, batch))
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3a", "cfg3b", "cfg4"])
+def test_benchmark_layer_at_batch_64(B, name):
+    """Batch 64, the paper's second evaluation batch size (section 6); cfg5a and cfg5b are defined at 64."""
+    check(B, workloads.with_batch(workloads.LAYERS[name], 64))
 
 
 # ---- explicit variant ------------------------------------------------------------------------
@@ -272,7 +315,7 @@ def test_explicit_variant_small(B, case):
     check(B, workloads.small_layer(name, *dims, seed_id=830), explicit=True)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3a", "cfg3b"])
+@pytest.mark.parametrize("name", list(workloads.LAYERS))
 def test_explicit_variant_benchmark_layers(B, name):
     check(B, workloads.LAYERS[name], explicit=True)
 
@@ -520,18 +563,12 @@ def test_tiles_holding_several_images(B):
               workloads.small_layer("g_b", 7, 5, 6, 64, 72, 3, 3, 1, 1, 1, dtype="f16", seed_id=871),
               workloads.small_layer("g_c", 9, 3, 3, 128, 64, 3, 3, 1, 0, 1, seed_id=872),            # P = Q = 1
               workloads.small_layer("g_d", 3, 9, 9, 64, 136, 3, 3, 1, 2, 2, seed_id=873)]           # dilated
-    names = [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
-    try:
-        for cap in (0, 1, 3):
-            B.iconv_set_max_workgroups(cap)
-            for v in [-1] + [i for i, nm in enumerate(names) if nm.startswith("p")]:
-                B.iconv_set_variant(v)
-                for L in shapes:
-                    print("cap", cap, "variant", names[v] if v >= 0 else "auto", L.name, flush=True)
-                    check(B, L)
-    finally:
-        B.iconv_set_variant(-1)
-        B.iconv_set_max_workgroups(0)
+    names = variant_names(B)
+    for cap in (0, 1, 3):
+        for v in [-1] + [i for i, nm in enumerate(names) if nm.startswith("p")]:
+            for L in shapes:
+                print("cap", cap, "variant", names[v] if v >= 0 else "auto", L.name, flush=True)
+                check(B, L, variant=v, cap=cap)
 
 
 def _random_shapes(count, seed):
@@ -555,14 +592,10 @@ def test_random_shapes_through_the_default_choice_and_forced_kernels(B):
     1 x S and R x 1 filters, K not a multiple of four) through the library's own kernel choice, and
     a third of them through every patch-reuse and per-tap kernel that accepts them."""
     shapes = _random_shapes(48, 20211)
-    names = [B.iconv_variant_name(v) for v in range(B.iconv_num_variants())]
-    try:
-        for i, dims in enumerate(shapes):
-            L = workloads.small_layer(f"rnd{i}", *dims, dtype="bf16" if i % 2 == 0 else "f16", seed_id=900 + i)
-            forced = [-1] + (list(range(len(names))) if i % 3 == 0 and L.C % 8 == 0 else [])
-            for v in forced:
-                B.iconv_set_variant(v)
-                print("shape", dims, "variant", names[v] if v >= 0 else "auto", flush=True)
-                check(B, L)
-    finally:
-        B.iconv_set_variant(-1)
+    names = variant_names(B)
+    for i, dims in enumerate(shapes):
+        L = workloads.small_layer(f"rnd{i}", *dims, dtype="bf16" if i % 2 == 0 else "f16", seed_id=900 + i)
+        forced = [-1] + (list(range(len(names))) if i % 3 == 0 and L.C % 8 == 0 else [])
+        for v in forced:
+            print("shape", dims, "variant", names[v] if v >= 0 else "auto", flush=True)
+            check(B, L, variant=v)
