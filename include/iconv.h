@@ -104,6 +104,21 @@ int iconv_fwd_explicit(const void *x_nhwc, const void *w_krsc, void *y_npqk,
                        int N, int H, int W, int C, int K, int R, int S,
                        int stride, int pad, int dilation, int dtype, void *stream);
 
+/* iconv_fwd_explicit for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc) and therefore have no workspace
+ * to pass: the lowered matrix goes into a buffer of ICONV_NOALLOC_WORKSPACE_BYTES that is part of
+ * the library's device image (one per GPU, held until the process ends).  The call allocates and
+ * frees nothing and runs the same two kernels as iconv_fwd_explicit, with the same result contract.
+ * Layers whose lowered matrix, iconv_workspace_bytes(ICONV_ALGO_EXPLICIT, ...), exceeds that size
+ * return ICONV_ERR_WORKSPACE and launch nothing.  Every call on a GPU uses that GPU's one buffer:
+ * calls that overlap on the same GPU (two streams, two threads) race on it and must be ordered by
+ * the caller; calls on different GPUs are independent.  The buffer's address is looked up on the
+ * first call on each device (no allocation; make that first call outside a graph capture). */
+#define ICONV_NOALLOC_WORKSPACE_BYTES (16u << 20)
+int iconv_fwd_explicit_noalloc(const void *x_nhwc, const void *w_krsc, void *y_npqk,
+                               int N, int H, int W, int C, int K, int R, int S,
+                               int stride, int pad, int dilation, int dtype, void *stream);
+
 /* Only the first half of the explicit variant (the lowering kernel), for timing it alone. */
 int iconv_im2col(const void *x_nhwc, void *workspace, size_t workspace_bytes,
                  int N, int H, int W, int C, int R, int S,

@@ -37,6 +37,8 @@ _lib.iconv_workspace_bytes.restype = _sz
 _lib.iconv_workspace_bytes.argtypes = [_i] * 12
 _lib.iconv_fwd_explicit.restype = _i
 _lib.iconv_fwd_explicit.argtypes = [_p, _p, _p, _p, _sz] + [_i] * 11 + [_p]
+_lib.iconv_fwd_explicit_noalloc.restype = _i
+_lib.iconv_fwd_explicit_noalloc.argtypes = [_p, _p, _p] + [_i] * 11 + [_p]
 _lib.iconv_fwd_channel_last.restype = _i
 _lib.iconv_fwd_channel_last.argtypes = [_p, _p, _p] + [_i] * 11 + [_p]
 _lib.iconv_im2col.restype = _i
@@ -58,7 +60,9 @@ _lib.iconv_status_string.restype = ctypes.c_char_p
 _lib.iconv_status_string.argtypes = [_i]
 
 # symbols declared in include/iconv.h and include/iconv_bench.h
-EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_im2col",
+NOALLOC_WORKSPACE_BYTES = 16 << 20
+EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit",
+           "iconv_fwd_explicit_noalloc", "iconv_im2col",
            "iconv_kernel_for", "iconv_status_string"]
 EXPORTS_BENCH = ["iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy", "iconv_probe_mfma"]
 
@@ -142,6 +146,17 @@ def iconv_fwd_explicit(x, w, y, workspace, workspace_bytes, N, H, W, C, K, R, S,
                        stream=None) -> None:
     rc = iconv_fwd_explicit_raw(x, w, y, workspace, workspace_bytes, N, H, W, C, K, R, S, stride, pad, dilation,
                                 dtype, stream)
+    if rc != 0:
+        raise IconvError(rc)
+
+
+def iconv_fwd_explicit_noalloc_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream=None) -> int:
+    return _lib.iconv_fwd_explicit_noalloc(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride, pad, dilation, dtype,
+                                           _stream(stream))
+
+
+def iconv_fwd_explicit_noalloc(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream=None) -> None:
+    rc = iconv_fwd_explicit_noalloc_raw(x, w, y, N, H, W, C, K, R, S, stride, pad, dilation, dtype, stream)
     if rc != 0:
         raise IconvError(rc)
 

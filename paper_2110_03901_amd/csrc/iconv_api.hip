@@ -1,4 +1,6 @@
 // C ABI of the library: argument checking, path selection, launches.  See include/iconv.h.
+#include <atomic>
+
 #include "iconv_bench.h"
 #include "iconv_common.h"
 #include "iconv_host.h"
@@ -10,6 +12,27 @@ namespace {
 // Launch width asked for by the iconv_fwd_ex call that is running on this thread (0 = fill the
 // device).  Set and restored inside that one call, so no call sees another's value.
 thread_local int tl_max_workgroups = 0;
+
+// Workspace of iconv_fwd_explicit_noalloc: part of the device image, one copy per GPU.  In host code
+// the name below is only a handle for hipGetSymbolAddress; the device address it yields (different on
+// every GPU) is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[ICONV_NOALLOC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr.
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // concurrent first calls store the same address
+    return p;
+}
 
 int out_dim(int in, int filt, int stride, int pad, int dil) {
     long span = (long)in + 2L * pad - (long)dil * (filt - 1) - 1;
@@ -187,6 +210,21 @@ int iconv_fwd_explicit(const void* x, const void* w, void* y, void* workspace, s
     if (!workspace || workspace_bytes < need) return ICONV_ERR_WORKSPACE;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(workspace)) return ICONV_ERR_ALIGN;
     return run_explicit(x, w, y, workspace, s, in_t, out_t, (hipStream_t)stream);
+}
+
+int iconv_fwd_explicit_noalloc(const void* x, const void* w, void* y, int N, int H, int W, int C, int K, int R, int S,
+                               int stride, int pad, int dilation, int dtype, void* stream) {
+    if (!x || !w || !y) return ICONV_ERR_NULL;
+    ConvShape s;
+    int in_t, out_t;
+    size_t need = 0;
+    int rc = explicit_shape(N, H, W, C, K, R, S, stride, pad, dilation, dtype, &s, &in_t, &out_t, &need);
+    if (rc != ICONV_OK) return rc;
+    if (need > (size_t)ICONV_NOALLOC_WORKSPACE_BYTES) return ICONV_ERR_WORKSPACE;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return ICONV_ERR_ALIGN;
+    void* ws = scratch_on_current_device();
+    if (!ws) return ICONV_ERR_LAUNCH;
+    return run_explicit(x, w, y, ws, s, in_t, out_t, (hipStream_t)stream);
 }
 
 int iconv_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
