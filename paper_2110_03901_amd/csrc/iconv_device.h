@@ -10,9 +10,16 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 // against num_records in bytes
 constexpr int kRsrcFlags = 0x00020000;
 
-// 16-byte-chunk swizzle of a tile row: keeps both the row-contiguous writes of the loader and
-// the column-of-rows ds_read_b128 of the MFMA operand fetch spread over all banks.
+// 16-byte-chunk swizzle of a tile row of CPR chunks.  The loader writes rows contiguously (lane-linear
+// LDS-DMA, always conflict-free); the MFMA operand fetch is a ds_read_b128 of 32 consecutive rows x
+// one chunk per half-wave, which the LDS serves in passes of 16 lanes: lanes 0-3, 12-15, 20-27 and
+// lanes 4-11, 16-19, 28-31 of each half-wave (measured on gfx950 by timing lane pairs that share a
+// bank).  A pass is conflict-free when its 16 lanes hit 16 different 16-byte slots of the 256-byte
+// bank window.  128-byte rows (and wider): XOR the row number, folded with row >> 3.  64-byte rows:
+// four consecutive rows fill a window, so the term must be constant over them and differ between
+// the four row quads of a pass (quads 0, 3, 5, 6 or 1, 2, 4, 7): the quad number's low two bits.
 template <int CPR> __device__ __forceinline__ int swz(int row, int chunk) {
+    if (CPR == 4) return chunk ^ ((row >> 2) & 3);
     constexpr int RP = (8 / CPR) > 0 ? (8 / CPR) : 1;  // tile rows per 128 bytes
     return chunk ^ (((row / RP) ^ (row >> 3)) & (CPR - 1));
 }

@@ -23,8 +23,18 @@
 // LDS.  Patch slice and filter slice use the same layout: rows (a pixel, or a filter) of 64
 // bytes = four 16-byte chunks of 8 channels, chunk c of row i stored at chunk c ^ ((i >> 2) & 3);
 // patch rows are padded to a multiple of 16 pixels.
-// An operand read has 16 consecutive lanes on 16 consecutive rows and the same chunk, which
-// then fall on 16 different 16-byte positions of the 256-byte bank window.
+// A ds_read_b128 is served in four passes of 16 lanes (lanes 0-3, 12-15, 20-27 / 4-11, 16-19,
+// 28-31 of each half-wave, as measured on this chip), and a pass is conflict-free when its 16
+// lanes fall on 16 different 16-byte positions of the 256-byte bank window.  With pixels that
+// are consecutive in LDS the layout above achieves that.  The 32 pixels of a fragment are
+// consecutive in the OUTPUT block, though: where they run from one block row into the next,
+// their patch pixels jump by PWp - TW, which shifts the swizzle term and makes two lane groups of
+// a pass collide (three of seven fragments for 56-wide rows in 64-pixel patch rows).  When
+// TW = 8 (mod 16) at stride 1 the jump is 8 (mod 16) pixels, i.e. exactly bit 1 of the swizzle
+// term, and storing ODD patch rows with bit 1 of the chunk number flipped ("skew") cancels it:
+// the term then is the one the pixel would have in a patch with rows of TW pixels, where the
+// fragment's pixels ARE consecutive.  A filter row r reads patch rows r*dil further down, so for
+// odd r*dil the flip coincides with the K-step bit (chunk 2*kk + l/32) and costs nothing.
 #include <atomic>
 #include <type_traits>
 
@@ -53,6 +63,7 @@ struct ResGeom {
     int slice_bytes;     // LDS bytes of one patch region (multiple of 1024)
     int w_bytes;         // LDS bytes of the filters: R*S*C*128
     int patch_loads;     // wave-wide loads per patch slice: PH * PWp / 16
+    int skew;            // 1: odd patch rows store their chunks with bit 1 of the chunk number flipped (see the kernel)
     float inv_tw;
 };
 
@@ -141,7 +152,8 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
             const bool row_ok = (unsigned)h < (unsigned)s.H;                // uniform
             const uint32_t base = (uint32_t)(((tc.n * s.H + h) * s.W + w0) * s.C + ks * 32) * 2u;   // uniform; wraps when out of range
             const bool ok = row_ok & ((unsigned)(w0 + l_row) < (unsigned)s.W);
-            dma16(x_rsrc, ok ? base + x_lane : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)(region + (uint32_t)(j * 1024))));
+            const uint32_t flip = (uint32_t)(g.skew & row & 1) << 5;       // odd patch rows: chunk bit 1 flipped (32 bytes)
+            dma16(x_rsrc, ok ? base + (x_lane ^ flip) : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)(region + (uint32_t)(j * 1024))));
             grp += dgrp; row += drow;
             if (grp >= groups) { grp -= groups; ++row; }
         }
@@ -194,7 +206,8 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
 #pragma unroll
         for (int sc = 0; sc < S_; ++sc) {
             const int pix = t < npx ? (th * g.PWp + tw) * s.stride + sc * s.dil : sc * s.dil;
-            a_addr[mf][sc] = (uint32_t)(pix * 64 + ((fk ^ ((pix >> 2) & 3)) << 4));
+            const int odd_row = t < npx ? (g.skew & th & 1) << 1 : 0;           // skew implies stride 1: patch row = th
+            a_addr[mf][sc] = (uint32_t)(pix * 64 + ((fk ^ ((pix >> 2) & 3) ^ odd_row) << 4));
         }
     }
     const uint32_t row_step = (uint32_t)(s.dil * g.PWp * 64);
@@ -229,20 +242,26 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
         const uint32_t pa = lds_base + (uint32_t)(g.w_bytes + (p % g.NR) * g.slice_bytes);   // LDS address of the patch region
         const char* pb = lds_b + ks * RS * 4096;
         frag_t af[MF], b0, b1;
-        // (one instruction, (a ^ b) + c, written out so that the optimiser neither splits it nor keeps
-        // the xor-ed variants of all addresses in registers across the loop)
-        auto fetch_a = [&](int mf, int sc, int kk, uint32_t roff) {
+        // (one instruction, (a ^ mask) + row offset, written out so that the optimiser neither splits it
+        // nor keeps the xor-ed variants of all addresses in registers across the loop; mask is 0 or 32 in a
+        // scalar register -- K step and row skew -- and the row offset travels in a vector register,
+        // because a VOP3 instruction reads one scalar operand at most)
+        auto fetch_a = [&](int mf, int sc, uint32_t mask, uint32_t roff_v) {
             uint32_t addr;
-            if (kk) asm volatile("v_xad_u32 %0, %1, 32, %2" : "=v"(addr) : "v"(a_addr[mf][sc]), "s"(roff));
-            else asm volatile("v_add_u32 %0, %1, %2" : "=v"(addr) : "s"(roff), "v"(a_addr[mf][sc]));
+            asm volatile("v_xad_u32 %0, %1, %2, %3" : "=v"(addr) : "v"(a_addr[mf][sc]), "s"(mask), "v"(roff_v));
             return *reinterpret_cast<const frag_t __attribute__((address_space(3)))*>(addr);
         };
         auto fetch_b = [&](int tap, int kk) {
             return *reinterpret_cast<const frag_t*>(pb + tap * 4096 + (kk ? b_lane1 : b_lane0));
         };
+        // flipped(r): the patch rows filter row r reads have chunk bit 1 flipped relative to filter row 0
+        // (skewed layout, odd r*dil), which swaps the roles of the two K steps in the address arithmetic.
+        auto flipped = [&](int r) { return (uint32_t)(g.skew & (min(r, s.R - 1) * s.dil) & 1) << 5; };
         auto row = [&](int r, auto first) {
             const int r_next = min(r + 1, s.R - 1);
-            const uint32_t roff = pa + (uint32_t)r * row_step, roff_next = pa + (uint32_t)r_next * row_step;
+            uint32_t roff = pa + (uint32_t)r * row_step, roff_next = pa + (uint32_t)r_next * row_step;
+            asm volatile("" : "+v"(roff), "+v"(roff_next));       // one copy each in vector registers for the whole row
+            const uint32_t mask_c = flipped(r), mask_n = flipped(r + 1);
 #pragma unroll
             for (int st = 0; st < 2 * S_; ++st) {
                 const bool wrap = st + 1 == 2 * S_;                   // next step: first of the next row
@@ -261,14 +280,14 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
                     } else {
                         acc[mf] = Elem<T>::mfma32(bc, af[mf], acc[mf]);
                     }
-                    af[mf] = fetch_a(mf, sc_n, kk_n, wrap ? roff_next : roff);
+                    af[mf] = fetch_a(mf, sc_n, (wrap ? mask_n : mask_c) ^ (uint32_t)(kk_n << 5), wrap ? roff_next : roff);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         };
         b0 = fetch_b(0, 0);
 #pragma unroll
-        for (int mf = MF0; mf < MF1; ++mf) af[mf] = fetch_a(mf, 0, 0, pa);
+        for (int mf = MF0; mf < MF1; ++mf) af[mf] = fetch_a(mf, 0, 0u, pa);
         __builtin_amdgcn_sched_barrier(0);
         if (ks == 0) row(0, std::true_type{});  // a block's first step starts the accumulators
         else row(0, std::false_type{});
@@ -377,6 +396,7 @@ bool plan_res(const ConvShape& s, int MF, ResGeom* g, double* cost_out) {
             g->KS = KS; g->NR = NR; g->slice_bytes = (int)slice_bytes; g->w_bytes = (int)w_lds;
             g->patch_loads = (int)patch_loads;
             g->inv_tw = 1.0f / (float)tw;
+            g->skew = (s.stride == 1 && (tw & 15) == 8) ? 1 : 0;
         }
     }
     if (!found) return false;
