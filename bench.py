@@ -30,10 +30,20 @@ if ROOT not in sys.path:
 PEAK_MFMA_TFLOPS = 2516.6   # bf16/fp16 dense MFMA, MI355X datasheet (256 CU x 2.4 GHz x 4096 flop/clk)
 PEAK_HBM_GBS = 8000.0       # HBM3E, MI355X datasheet
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script, scaled by the same counters' reading for the copy probe (see profiles/): layer -> bytes
-MEASURED_TRAFFIC_BYTES = {"cfg2": 39_350_000, "cfg3a": 41_090_000, "cfg3b": 66_720_000, "cfg4": 59_940_000,
-                          "cfg5a": 242_640_000, "cfg5b": 47_560_000}   # profiles/bench_all_layers_pmc.txt
+def measured_traffic_bytes():
+    """HBM bytes per launch of each layer's kernel as the last committed rocprofv3 --pmc runs of this script
+    measured them (FETCH_SIZE / WRITE_SIZE, scaled by the same counters' reading for the copy probe): the lines
+    `traffic_bytes <layer> <bytes>` of profiles/bench_all_layers_pmc.txt.  Missing file or layer -> None."""
+    out = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "bench_all_layers_pmc.txt")) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes":
+                    out[parts[1]] = int(parts[2])
+    except OSError:
+        pass
+    return out
 
 
 def main():
@@ -123,9 +133,10 @@ def main():
     code, host_in, run, bufs = prepare(L)
 
     # ---- headline ------------------------------------------------------------------------------
-    ms = time_steps(run, args.steps, args.warmup)
+    # (the graph of exactly --steps launches is replayed five times; the median replay is reported)
+    ms = time_steps(run, args.steps, args.warmup, repeats=1 if args.eager else 5)
     bound, tflops, gbs = bound_of(L, ms)
-    traffic = MEASURED_TRAFFIC_BYTES.get(head_name)
+    traffic = measured_traffic_bytes().get(head_name)
     if bound == "mfma":
         roofline = {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(tflops / PEAK_MFMA_TFLOPS, 4), "traffic": traffic}
@@ -137,6 +148,8 @@ def main():
     roofline["flops"] = L.flops
     roofline["mfma_frac"] = round(tflops / PEAK_MFMA_TFLOPS, 4)
     roofline["hbm_frac_algorithmic"] = round(gbs / PEAK_HBM_GBS, 4)
+    roofline["note"] = ("warm replays: x, w and y of consecutive launches stay in the 256 MiB last-level cache, so `achieved` is "
+                        "algorithmic bytes over time, not DRAM traffic; see `cold` for launches on rotating buffers")
 
     out = {
         "metric": "effective conv TFLOP/s (2*N*P*Q*K*C*R*S / time), 1 MI355X",
@@ -145,7 +158,8 @@ def main():
         "dtype": L.dtype, "data": "synthetic",
         "config": {"workload": f"{head_name}: N={L.N} H=W={L.H} C={L.C} K={L.K} {L.R}x{L.S} "
                                f"stride={L.stride} pad={L.pad} dil={L.dilation}, {L.dtype} in / fp32 acc+out, NHWC/KRSC",
-                   "im2col_workspace_bytes": 0, "timing": "eager launches" if args.eager else "HIP graph replay"},
+                   "im2col_workspace_bytes": 0,
+                   "timing": "eager launches" if args.eager else "HIP graph replay, median of 5 replays of the graph of `steps` launches"},
         "roofline": roofline,
     }
 
@@ -171,19 +185,27 @@ def main():
         del sets
         torch.cuda.empty_cache()
 
-    # ---- explicit im2col + GEMM on the headline layer (the comparison the paper argues against) --
+    # ---- explicit im2col + GEMM (the comparison the paper argues against): headline layer here, every layer below --
+    def explicit_of(Li, code_i, xd, wd, y, ms_implicit, n_exp):
+        sa = Li.shape_args()
+        ws_bytes = B.iconv_workspace_bytes(B.ALGO_EXPLICIT, *sa, code_i)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+        ms_full = time_steps(lambda: B.iconv_fwd_explicit(xd, wd, y, ws, ws_bytes, *sa, code_i), n_exp, 5, repeats=3)
+        ms_low = time_steps(lambda: B.iconv_im2col(xd, ws, ws_bytes, Li.N, Li.H, Li.W, Li.C, Li.R, Li.S, Li.stride, Li.pad,
+                                                   Li.dilation, code_i), n_exp, 5, repeats=3)
+        del ws
+        torch.cuda.empty_cache()
+        x_bytes = Li.N * Li.H * Li.W * Li.C * Li.elt_bytes()
+        return {"workspace_bytes": ws_bytes, "ms_total": round(ms_full, 5), "ms_im2col": round(ms_low, 5),
+                "ms_gemm": round(ms_full - ms_low, 5),
+                # the lowering kernel reads x once and writes the lowered matrix; the GEMM reads the matrix and writes y
+                "im2col_gbs": round((x_bytes + ws_bytes) / (ms_low * 1e-3) / 1e9, 1),
+                "gemm_gbs": round((ws_bytes + Li.M * Li.K * 4) / (max(ms_full - ms_low, 1e-6) * 1e-3) / 1e9, 1),
+                "slowdown_vs_implicit": round(ms_full / ms_implicit, 3)}
+
     if not args.no_explicit:
         xd, wd, y = bufs
-        sa = L.shape_args()
-        ws_bytes = B.iconv_workspace_bytes(B.ALGO_EXPLICIT, *sa, code)
-        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
-        n_exp = max(20, args.steps // 10)
-        ms_full = time_steps(lambda: B.iconv_fwd_explicit(xd, wd, y, ws, ws_bytes, *sa, code), n_exp, 10)
-        ms_low = time_steps(lambda: B.iconv_im2col(xd, ws, ws_bytes, L.N, L.H, L.W, L.C, L.R, L.S, L.stride, L.pad,
-                                                   L.dilation, code), n_exp, 10)
-        out["explicit"] = {"workspace_bytes": ws_bytes, "ms_total": round(ms_full, 5), "ms_im2col": round(ms_low, 5),
-                           "slowdown_vs_implicit": round(ms_full / ms, 3)}
-        del ws
+        out["explicit"] = explicit_of(L, code, xd, wd, y, ms, max(20, args.steps // 10))
 
     # ---- all benchmark layers, briefly -----------------------------------------------------------
     if not args.no_layers:
@@ -195,8 +217,17 @@ def main():
             bi, tf, gb = bound_of(Li, mi)
             tf_real = Li.flops_real / (mi * 1e-3) / 1e12
             layers[name] = {"us": round(mi * 1e3, 3), "tflops": round(tf_real, 2), "bound": bi,
-                            "mfma_frac": round(tf / PEAK_MFMA_TFLOPS, 4),
+                            "kernel": B.iconv_kernel_for(*Li.shape_args(), B.DTYPE_CODES[Li.dtype]),
+                            # fraction of the MFMA peak by the flops of the real channels (cfg5a: 3 of the 4 stored)
+                            "mfma_frac": round(tf_real / PEAK_MFMA_TFLOPS, 4),
                             "gbs_algorithmic": round(gb, 1), "hbm_frac": round(gb / PEAK_HBM_GBS, 4)}
+            if Li.flops_real != Li.flops:
+                layers[name]["mfma_frac_with_padding_channels"] = round(tf / PEAK_MFMA_TFLOPS, 4)
+            if not args.no_explicit and name != head_name:
+                ci = B.DTYPE_CODES[Li.dtype]
+                layers[name]["explicit"] = explicit_of(Li, ci, keep[0], keep[1], keep[2], mi, 20)
+            elif not args.no_explicit:
+                layers[name]["explicit"] = out["explicit"]
             del keep
             torch.cuda.empty_cache()
         out["layers"] = layers
@@ -289,7 +320,8 @@ def main():
         torch.cuda.synchronize()
         out["calibration"] = {"copy_bytes_each_way": n, "launches": 5}
 
-    # ---- the CPU oracle on the same layer, on this machine's host cores ------------------------------
+    # ---- the CPU oracle on this machine's host cores: the headline layer repeatedly (about 10 s), then every other
+    # benchmark layer once (a full evaluation each: 0.15 M ... 19 G multiply-accumulates, under a second apiece)
     if not args.no_cpu:
         from oracle.conv_ref import conv_ref, threads
         x, w = host_in
@@ -305,6 +337,17 @@ def main():
         out["cpu_baseline"] = {"value": round(cpu_tflops, 5), "unit": "TFLOP/s", "cores": threads(), "kind": "oracle",
                                "sample": f"{reps} full evaluation(s) of {head_name} ({L.flops / 2e9:.2f} GMAC each), "
                                          f"{el:.1f} s wall, fp64 7-loop C/OpenMP"}
+        per_layer = {}
+        for name, Li in workloads.LAYERS.items():
+            if name == head_name:
+                per_layer[name] = {"ms": round(el / reps * 1e3, 2), "tflops": round(cpu_tflops, 5), "evaluations": reps}
+                continue
+            xi, wi = workloads.make_inputs(Li)
+            t1 = time.perf_counter()
+            conv_ref(xi, wi, Li.stride, Li.pad, Li.dilation)
+            dt = time.perf_counter() - t1
+            per_layer[name] = {"ms": round(dt * 1e3, 2), "tflops": round(Li.flops_real / dt / 1e12, 5), "evaluations": 1}
+        out["cpu_baseline"]["layers"] = per_layer
     print(json.dumps(out), flush=True)
 
 

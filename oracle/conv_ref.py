@@ -13,12 +13,15 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conv_ref.c")
-_LIB = os.path.join(_HERE, "libconv_ref.so")
+# CONV_REF_LIB: a differently built copy of the same source (the sanitizer leg of the tests loads one)
+_LIB = os.environ.get("CONV_REF_LIB") or os.path.join(_HERE, "libconv_ref.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile conv_ref.c with gcc (OpenMP, no fast-math: the fp64 sum keeps its loop order)."""
+    if os.environ.get("CONV_REF_LIB"):
+        return _LIB                      # built by whoever set the variable
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",

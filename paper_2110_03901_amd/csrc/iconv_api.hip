@@ -1,6 +1,8 @@
 // C ABI of the library: argument checking, path selection, launches.  See include/iconv.h.
 #include <atomic>
 
+#include <initializer_list>
+
 #include "iconv_bench.h"
 #include "iconv_common.h"
 #include "iconv_host.h"
@@ -59,14 +61,19 @@ int make_shape(int N, int H, int W, int C, int K, int R, int S, int stride, int 
     if (stride < 1 || dil < 1 || pad < 0) return ICONV_ERR_SHAPE;
     const int P = out_dim(H, R, stride, pad, dil), Q = out_dim(W, S, stride, pad, dil);
     if (P < 1 || Q < 1) return ICONV_ERR_SHAPE;
+    // every tensor, and the padded coordinate space the kernels index, must stay below 2^31 elements; the
+    // products are formed one factor at a time so that absurd arguments cannot overflow on the way
     const long long lim = 1LL << 31;
-    const long long xe = (long long)N * H * W * C, we = (long long)K * R * S * C, ye = (long long)N * P * Q * K;
-    const long long le = (long long)N * P * Q * R * S * C;  // lowered matrix (explicit variant)
-    if (xe >= lim || we >= lim || ye >= lim) return ICONV_ERR_UNSUPPORTED;
-    // padded coordinates must stay inside int32 arithmetic as well
-    if ((long long)(H + 2LL * pad + (long long)dil * R) * (W + 2LL * pad + (long long)dil * S) * C >= lim * 4)
-        return ICONV_ERR_UNSUPPORTED;
-    (void)le;
+    auto fits = [](long long limit, std::initializer_list<long long> factors) {
+        long long prod = 1;
+        for (long long f : factors) {
+            if (f <= 0 || prod > limit / f) return false;       // prod * f would reach the limit (or f is not a size)
+            prod *= f;
+        }
+        return prod < limit;
+    };
+    if (!fits(lim, {N, H, W, C}) || !fits(lim, {K, R, S, C}) || !fits(lim, {N, P, Q, K})) return ICONV_ERR_UNSUPPORTED;
+    if (!fits(lim * 4, {H + 2LL * pad + (long long)dil * R, W + 2LL * pad + (long long)dil * S, C})) return ICONV_ERR_UNSUPPORTED;
     s->N = N; s->H = H; s->W = W; s->C = C; s->K = K; s->R = R; s->S = S;
     s->stride = stride; s->pad = pad; s->dil = dil; s->P = P; s->Q = Q;
     s->PQ = P * Q; s->M = N * P * Q; s->Kg = C * R * S;

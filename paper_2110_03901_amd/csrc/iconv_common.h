@@ -82,6 +82,11 @@ int resident_choose(const ConvShape& s);   // best variant or -1
 hipError_t launch_resident(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
                            hipStream_t stream);
 
+// Resident-filter kernels phased by filter row, one LDS row per pixel (C == 32 or 64); variants 0, 1 = 7, 8 fragments.
+bool rowres_supported(const ConvShape& s, int v);
+bool rowres_plan_cost(const ConvShape& s, int v, double* cost, long* blocks);
+hipError_t launch_rowres(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t stream);
+
 // Merged-tap kernel for C == 4 first layers (stride 2, dilation 1, even W, S + (pad & 1) <= 8).
 bool stem_supported(const ConvShape& s);
 hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,

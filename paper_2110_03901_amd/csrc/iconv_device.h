@@ -46,6 +46,29 @@ __device__ __forceinline__ void dma16s(rsrc_t rsrc, uint32_t voff, uint32_t soff
                  : "memory", "m0");
 }
 
+// Touches the first `BYTES` bytes of the kernel-argument segment, one scalar load per 64-byte line,
+// all in flight at once, and waits for them.  The compiler fetches arguments where they are first
+// used, behind branches, which at the start of a kernel costs one cold scalar-cache miss (about
+// 0.3 us) after the other; with every line requested up front there is one such wait and the
+// compiler's own loads hit.  The loaded words are not used.  The wait is part of the same asm
+// statement on purpose: a scalar load writes its destination when the data returns, so the
+// destination registers must stay reserved until then.
+template <int BYTES> __device__ __forceinline__ void touch_kernargs() {
+    static_assert(BYTES > 0 && BYTES <= 256, "one load per 64-byte line, four lines at most");
+    const auto* ka = (const __attribute__((address_space(4))) uint32_t*)__builtin_amdgcn_kernarg_segment_ptr();
+    uint32_t d0, d1, d2, d3;
+    if (BYTES <= 64)
+        asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(d0) : "s"(ka));
+    else if (BYTES <= 128)
+        asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %2, 0x40\n\ts_waitcnt lgkmcnt(0)" : "=&s"(d0), "=&s"(d1) : "s"(ka));
+    else if (BYTES <= 192)
+        asm volatile("s_load_dword %0, %3, 0x0\n\ts_load_dword %1, %3, 0x40\n\ts_load_dword %2, %3, 0x80\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(d0), "=&s"(d1), "=&s"(d2) : "s"(ka));
+    else
+        asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\ts_load_dword %3, %4, 0xc0\n\t"
+                     "s_waitcnt lgkmcnt(0)" : "=&s"(d0), "=&s"(d1), "=&s"(d2), "=&s"(d3) : "s"(ka));
+}
+
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");

@@ -449,42 +449,59 @@ hipError_t launch_res_mf(const void* x, const void* w, void* y, const ConvShape&
 }
 
 constexpr int kResMF[] = {7, 8};
-const char* const kResNames[] = {"r448x64_f7_4+4", "r512x64_f8_4+4"};
+// r: channel-slice phases (this file); t: filter-row phases, whole pixels per LDS row (iconv_rowres.hip)
+const char* const kResNames[] = {"r448x64_f7_4+4", "r512x64_f8_4+4", "t448x64_f7_4+4", "t512x64_f8_4+4"};
 
 }  // namespace
 
-int resident_num_variants() { return 2; }
+int resident_num_variants() { return 4; }
 const char* resident_variant_name(int v) { return kResNames[v]; }
 
 bool resident_supported(const ConvShape& s, int v) {
+    if (v >= 2) return rowres_supported(s, v - 2);
     ResGeom g;
-    return v >= 0 && v < 2 && plan_res(s, kResMF[v], &g, nullptr);
+    return v >= 0 && plan_res(s, kResMF[v], &g, nullptr);
 }
 
-// The variant with the lower modelled cost, or -1 when the layer does not fit the kernel.
-// Its blocks are large (448 or 512 pixels x all filters), so it is only offered when there are
+// The variant with the lower modelled cost, or -1 when the layer does not fit the kernels.
+// Their blocks are large (448 or 512 pixels x all filters), so they are only offered when there are
 // enough of them to occupy most of the device -- or half of it, when the 256-pixel tiles of the
 // patch-reuse kernel that would run instead no longer fit one round of workgroups (measured on the
 // 56 x 56, 64 -> 64 layer: batches 20 .. 27 take 13.2 .. 14.3 us here against 16.6 us there).
+// Layers with 32 or 64 channels take the filter-row-phased kernel, which starts its first MFMA sooner.
 int resident_choose(const ConvShape& s) {
-    ResGeom g7, g8;
-    double c7 = 0, c8 = 0;
     const long cus = device_cus();
     // full-width tiles of 256 / Q output rows, as the patch-reuse planner forms them for narrow maps
     const long th = s.Q <= 256 ? 256 / s.Q : 1;
     const long patch_tiles = (long)s.N * ((s.P + th - 1) / th) * ((s.Q + 255) / 256);
     const long enough = patch_tiles > cus ? cus / 2 : cus * 3 / 4;
-    const bool ok7 = plan_res(s, 7, &g7, &c7) && g7.total_tiles >= enough;
-    const bool ok8 = plan_res(s, 8, &g8, &c8) && g8.total_tiles >= enough;
-    if (!ok7 && !ok8) return -1;
-    if (ok7 && ok8) return c7 <= c8 ? 0 : 1;
-    return ok7 ? 0 : 1;
+    int best = -1;
+    double best_cost = 0;
+    for (int v = 0; v < 4; ++v) {
+        double c = 0;
+        long blocks = 0;
+        bool ok;
+        if (v >= 2) {
+            ok = rowres_plan_cost(s, v - 2, &c, &blocks);
+        } else {
+            ResGeom g;
+            ok = plan_res(s, kResMF[v], &g, &c);
+            blocks = ok ? g.total_tiles : 0;
+        }
+        if (!ok || blocks < enough) continue;
+        if (best < 0 || c < best_cost || (v >= 2 && best < 2 && c <= best_cost)) {
+            best = v;
+            best_cost = c;
+        }
+    }
+    return best;
 }
 
 hipError_t launch_resident(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
                            hipStream_t st) {
+    if (v >= 2) return launch_rowres(x, w, y, s, in_t, out_t, v - 2, st);
     ResGeom g;
-    if (v < 0 || v >= 2 || !plan_res(s, kResMF[v], &g, nullptr)) return hipErrorInvalidConfiguration;
+    if (v < 0 || !plan_res(s, kResMF[v], &g, nullptr)) return hipErrorInvalidConfiguration;
     if (v == 0) return launch_res_mf<7>(x, w, y, s, g, in_t, out_t, st);
     return launch_res_mf<8>(x, w, y, s, g, in_t, out_t, st);
 }

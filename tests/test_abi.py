@@ -128,8 +128,10 @@ def test_kernel_choice_follows_the_layer_class(lib):
     lib.iconv_variant_name.restype = ctypes.c_char_p
     table = {lib.iconv_variant_name(i).decode() for i in range(lib.iconv_num_variants())}
     bf16 = 1
-    # the benchmark layers: resident filters (r...), per-tap direct-to-LDS (d...), patch reuse (p...), merged taps
-    assert kernel_for(lib, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("r")
+    # the benchmark layers: resident filters (t...: phased by filter row; r...: by channel slice), per-tap
+    # direct-to-LDS (d...), patch reuse (p...), merged taps
+    assert kernel_for(lib, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("t448")
+    assert kernel_for(lib, 32, 56, 56, 96, 64, 1, 1, 1, 0, 1, bf16).startswith("r")            # 96 channels: channel slices
     assert kernel_for(lib, 32, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d128x128")
     assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("d256x256")
     assert kernel_for(lib, 8, 64, 64, 256, 256, 3, 3, 1, 2, 2, bf16).startswith("p256x128")
@@ -140,7 +142,7 @@ def test_kernel_choice_follows_the_layer_class(lib):
     # tile size follows the tile count: the same layers at other batch sizes
     assert kernel_for(lib, 8, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("p128x64")      # 196 tiles of 128 pixels
     assert kernel_for(lib, 16, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("p256x64")     # 112 resident blocks: too few
-    assert kernel_for(lib, 20, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("r")           # patch tiles need two rounds
+    assert kernel_for(lib, 20, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("t")           # patch tiles need two rounds
     assert kernel_for(lib, 64, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d256x128")  # 392 tiles of 128x128
     assert kernel_for(lib, 32, 56, 56, 256, 128, 1, 1, 1, 0, 1, bf16).startswith("d256x128")  # K = 128: no 256-wide tile
     assert kernel_for(lib, 32, 7, 7, 2048, 512, 1, 1, 1, 0, 1, bf16).startswith("d64x64")     # 1568 output pixels

@@ -168,23 +168,33 @@ def test_workgroups_walking_several_tiles(B):
 
 def test_resident_filter_kernels(B):
     """The resident-filter kernels (filters of 64 output channels and the input patch of a block in
-    LDS): both fragment counts, forced, on shapes with one to four channel slices, strides,
-    dilation, ragged blocks and K < 64, uncapped and with workgroups walking through several
-    blocks (the next block's first slice is loaded while the last slice is computed)."""
+    LDS), phased by channel slice ("r") or by filter row ("t"; 32 or 64 channels): all fragment counts,
+    forced, on shapes with one to four channel slices, strides, dilation, ragged blocks, block widths
+    with and without the skewed patch rows, tall filters and K < 64, uncapped and with workgroups
+    walking through several blocks (the next block is loaded while the last one is stored)."""
     shapes = [workloads.small_layer("r_a", 3, 20, 22, 64, 64, 3, 3, 1, 1, 1, seed_id=840),     # two slices
               workloads.small_layer("r_b", 2, 17, 19, 32, 40, 3, 3, 1, 1, 1, seed_id=841),     # one slice, K = 40
               workloads.small_layer("r_c", 2, 24, 24, 96, 64, 3, 3, 1, 2, 2, seed_id=842),     # three slices, dilated
               workloads.small_layer("r_d", 1, 33, 31, 64, 48, 3, 3, 2, 1, 1, seed_id=843),     # stride 2
               workloads.small_layer("r_e", 2, 30, 9, 128, 64, 1, 3, 1, 1, 1, dtype="f16", seed_id=844),   # 1x3, four slices
-              workloads.small_layer("r_f", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1, seed_id=845)]     # full-width blocks of 7 rows
+              workloads.small_layer("r_f", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1, seed_id=845),     # full-width blocks of 7 rows
+              workloads.small_layer("r_g", 2, 24, 24, 64, 64, 3, 3, 1, 2, 2, seed_id=846),     # 64 channels, dilated, 24-wide blocks
+              workloads.small_layer("r_h", 1, 30, 12, 32, 48, 5, 3, 1, 2, 1, dtype="f16", seed_id=847),   # five filter rows
+              workloads.small_layer("r_i", 3, 24, 24, 32, 64, 3, 3, 1, 1, 1, seed_id=848),     # 32 channels, skewed rows
+              workloads.small_layer("r_j", 2, 40, 40, 64, 60, 1, 1, 1, 0, 1, seed_id=849)]     # 1x1, K = 60
     names = variant_names(B)
-    res = [v for v, nm in enumerate(names) if nm.startswith("r")]
-    assert len(res) >= 2
+    res = [v for v, nm in enumerate(names) if nm[0] in "rt"]
+    assert len(res) == 4
+    ran = 0
     for cap in (0, 1, 3):
         for v in res:
             for L in shapes:
+                if not B.iconv_variant_accepts(v, *L.shape_args(), code_of(L)):
+                    continue
                 print("cap", cap, "variant", names[v], L.name, flush=True)
                 check(B, L, variant=v, cap=cap)
+                ran += 1
+    assert ran >= 3 * 15
 
 
 def test_merged_tap_workgroups_walking_several_blocks(B):
@@ -257,6 +267,9 @@ OUT16_CASES = [
     ("res_f7", "r448x64", 0, ("o_r7", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1)),
     ("res_f7_walk", "r448x64", 3, ("o_r7w", 3, 28, 28, 64, 48, 3, 3, 1, 1, 1)),
     ("res_f8_1x1", "r512x64", 0, ("o_r8", 2, 32, 32, 96, 64, 1, 1, 1, 0, 1)),
+    ("row_f7", "t448x64", 0, ("o_t7", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1)),
+    ("row_f7_walk_c32", "t448x64", 2, ("o_t7w", 3, 28, 28, 32, 48, 3, 3, 1, 1, 1)),
+    ("row_f8_1x1", "t512x64", 0, ("o_t8", 2, 32, 32, 64, 64, 1, 1, 1, 0, 1)),
     ("tap_256x256x32_staged", "d256x256x32", 0, ("o_t4", 2, 28, 28, 72, 264, 1, 1, 2, 0, 1)),
     ("tap_128x128_pf_staged", "d128x128x64_w64x32_s3_pf", 0, ("o_t8", 2, 30, 30, 128, 160, 3, 3, 2, 1, 1)),
     ("tap_128x64_scalar_tail", "d128x64x64", 0, ("o_t2", 2, 15, 17, 32, 42, 3, 3, 2, 1, 1)),
