@@ -451,10 +451,11 @@ hipError_t launch_res_mf(const void* x, const void* w, void* y, const ConvShape&
 constexpr int kResMF[] = {7, 8};
 // r: channel-slice phases (this file); t: filter-row phases, whole pixels per LDS row (iconv_rowres.hip)
 const char* const kResNames[] = {"r448x64_f7_4+4", "r512x64_f8_4+4", "t448x64_f7_4+4", "t512x64_f8_4+4"};
+constexpr int kNumRes = 4;
 
 }  // namespace
 
-int resident_num_variants() { return 4; }
+int resident_num_variants() { return kNumRes; }
 const char* resident_variant_name(int v) { return kResNames[v]; }
 
 bool resident_supported(const ConvShape& s, int v) {
@@ -477,7 +478,7 @@ int resident_choose(const ConvShape& s) {
     const long enough = patch_tiles > cus ? cus / 2 : cus * 3 / 4;
     int best = -1;
     double best_cost = 0;
-    for (int v = 0; v < 4; ++v) {
+    for (int v = 0; v < kNumRes; ++v) {
         double c = 0;
         long blocks = 0;
         bool ok;

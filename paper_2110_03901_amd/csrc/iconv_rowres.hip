@@ -374,6 +374,7 @@ irow_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     }
 }
 
+
 constexpr int kRowLdsLimit = 160 * 1024;
 
 // Chooses the output block TH x TW (TH*TW <= 64*MF) for a fragment count MF; cost model as for the

@@ -181,7 +181,9 @@ def test_resident_filter_kernels(B):
               workloads.small_layer("r_g", 2, 24, 24, 64, 64, 3, 3, 1, 2, 2, seed_id=846),     # 64 channels, dilated, 24-wide blocks
               workloads.small_layer("r_h", 1, 30, 12, 32, 48, 5, 3, 1, 2, 1, dtype="f16", seed_id=847),   # five filter rows
               workloads.small_layer("r_i", 3, 24, 24, 32, 64, 3, 3, 1, 1, 1, seed_id=848),     # 32 channels, skewed rows
-              workloads.small_layer("r_j", 2, 40, 40, 64, 60, 1, 1, 1, 0, 1, seed_id=849)]     # 1x1, K = 60
+              workloads.small_layer("r_j", 2, 40, 40, 64, 60, 1, 1, 1, 0, 1, seed_id=849),     # 1x1, K = 60
+              workloads.small_layer("r_k", 5, 56, 56, 64, 44, 3, 3, 1, 1, 1, seed_id=850),     # five blocks per image row group, K = 44
+              workloads.small_layer("r_l", 2, 50, 56, 32, 64, 5, 3, 1, 2, 1, dtype="f16", seed_id=851)]   # five filter rows, ragged last block
     names = variant_names(B)
     res = [v for v, nm in enumerate(names) if nm[0] in "rt"]
     assert len(res) == 4
