@@ -49,7 +49,12 @@ struct PatchGeom {
 // pixels that are `stride` apart, same chunk.  For an odd stride those pixels spread evenly over
 // the pixel-in-window positions, and XOR-ing the window number into the chunk bits alone makes
 // the 16 slots distinct; for an even stride they share few pixel-in-window positions, and the
-// window number has to be XOR-ed into all four slot bits.
+// window number has to be XOR-ed into all four slot bits.  (Where the 32 pixels of a fragment run
+// from one block row into the next, their patch pixels jump by PW - TW and two lane groups of a
+// pass can meet in a slot.  Taking the XOR term from the block-linear pixel index instead removes
+// those conflicts, was measured, and is 1-3 % SLOWER on the 64 x 64 dilated and the 7 x 7 layers:
+// the two extra integer operations per fragment and step, and per load in the loader waves, cost
+// more than the conflicts, which these loops hide under their MFMAs.)
 //
 // Wave roles.  The workgroup has WAVES_M*WAVES_N compute waves and NLD loader waves.  Loader waves
 // only issue the global -> LDS loads (their address arithmetic then overlaps the compute waves'
@@ -348,7 +353,6 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.G * g.TH * g.TW;
     int a_base[MI];                             // patch pixel of each A-fragment row at tap (0, 0)
-    int o_th[MI], o_tw[MI], o_gi[MI];           // the same row as (row, column) of the output block, and its image within the tile
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int t = (wave_m * MI + mi) * 32 + frow;
@@ -357,9 +361,6 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         const int gi = g.G > 1 ? (int)(((float)tv + 0.5f) * g.inv_th) : 0;
         const int th = tv - gi * g.TH;
         a_base[mi] = t < npx ? ((gi * g.PH + th * s.stride) * g.PW + tw * s.stride) : 0;
-        o_th[mi] = t < npx ? th : (1 << 20);    // rows past the block never pass the p < P test
-        o_tw[mi] = tw;
-        o_gi[mi] = gi;
     }
     int b_idx[NI][KI];                          // filter-fragment positions within a stage (16-byte units)
 #pragma unroll
@@ -408,8 +409,17 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            const int p = tc.p0 + o_th[mi], q = tc.q0 + o_tw[mi], n = tc.n + o_gi[mi];
-            if (p < s.P && q < s.Q && n < s.N) {
+            // (row, column) of the lane's pixel in the output block and its image within the tile: recomputed per tile
+            // rather than kept in registers through the K loop
+            int frow_v = frow;
+            asm volatile("" : "+v"(frow_v));
+            const int t = (wave_m * MI + mi) * 32 + frow_v;
+            const int tv = (int)(((float)t + 0.5f) * g.inv_tw);
+            const int o_tw = t - tv * g.TW;
+            const int o_gi = g.G > 1 ? (int)(((float)tv + 0.5f) * g.inv_th) : 0;
+            const int o_th = tv - o_gi * g.TH;
+            const int p = tc.p0 + o_th, q = tc.q0 + o_tw, n = tc.n + o_gi;
+            if (t < npx && p < s.P && q < s.Q && n < s.N) {
                 TO* yrow = y + (size_t)((n * s.P + p) * s.Q + q) * s.K;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
