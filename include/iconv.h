@@ -76,7 +76,11 @@ int iconv_fwd(const void *x_nhwc, const void *w_krsc, void *y_npqk,
               int stride, int pad, int dilation, int dtype, void *stream);
 
 /* Device bytes the caller must provide as workspace.  ICONV_ALGO_IMPLICIT: always 0.
- * ICONV_ALGO_EXPLICIT: the lowered matrix of section 2.1, M x (R*S*C) input elements.
+ * ICONV_ALGO_EXPLICIT: the lowered matrix of section 2.1, M x (R*S*C) input elements.  When
+ * R*S*C is not a multiple of 8 and the inputs are 16-bit, the rows of the lowered matrix are
+ * padded with zeros to the next multiple of 8 elements (the matrix cores read 16-byte runs),
+ * the total is rounded up to 16 bytes, and a copy of the K x (R*S*C) filter matrix with rows
+ * of the same padded length follows it: M*pitch*2 (rounded) + K*pitch*2 bytes.
  * Returns 0 also for invalid arguments. */
 size_t iconv_workspace_bytes(int algo, int N, int H, int W, int C, int K, int R, int S,
                              int stride, int pad, int dilation, int dtype);
@@ -119,7 +123,8 @@ int iconv_fwd_explicit_noalloc(const void *x_nhwc, const void *w_krsc, void *y_n
                                int N, int H, int W, int C, int K, int R, int S,
                                int stride, int pad, int dilation, int dtype, void *stream);
 
-/* Only the first half of the explicit variant (the lowering kernel), for timing it alone. */
+/* Only the first half of the explicit variant (the lowering kernel), for timing it alone;
+ * `workspace_bytes` must cover the lowered matrix (the padded rows, see above). */
 int iconv_im2col(const void *x_nhwc, void *workspace, size_t workspace_bytes,
                  int N, int H, int W, int C, int R, int S,
                  int stride, int pad, int dilation, int dtype, void *stream);

@@ -98,28 +98,55 @@ int run_conv(const void* x, const void* w, void* y, const ConvShape& s, int in_t
     return status_of(launch_direct(x, w, y, s, in_t, out_t, st));
 }
 
+// Workspace layout of the explicit variant: the lowered matrix, M rows of `pitch` elements, and -- when Kg is not
+// a multiple of eight 16-bit elements, so that the MFMA GEMM cannot read the caller's filter matrix as it is --
+// a copy of the K x Kg filter matrix with rows of the same pitch behind it.
+struct ExplicitLayout {
+    int pitch;              // elements per lowered row: Kg, or Kg rounded up to a multiple of 8 (16-bit inputs)
+    size_t lowered_bytes;   // M * pitch * element size, rounded up to 16 bytes
+    size_t filter_bytes;    // K * pitch * element size when the filters are copied, else 0
+    size_t total() const { return lowered_bytes + filter_bytes; }
+};
+ExplicitLayout explicit_layout(const ConvShape& s, int in_t) {
+    ExplicitLayout L;
+    const size_t e = (size_t)in_bytes(in_t);
+    const bool pad = in_t != IN_F32 && (s.Kg & 7) != 0;
+    L.pitch = pad ? (s.Kg + 7) & ~7 : s.Kg;
+    L.lowered_bytes = ((size_t)s.M * (size_t)L.pitch * e + 15) & ~(size_t)15;
+    L.filter_bytes = pad ? (size_t)s.K * (size_t)L.pitch * e : 0;
+    return L;
+}
+
 // Shape, type and lowered-matrix size of the explicit variant.  Returns an ICONV_* status.
 int explicit_shape(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dil, int dtype, ConvShape* s,
                    int* in_t, int* out_t, size_t* need) {
     int rc = make_shape(N, H, W, C, K, R, S, stride, pad, dil, s);
     if (rc != ICONV_OK) return rc;
     if (!dtype_types(dtype, in_t, out_t)) return ICONV_ERR_UNSUPPORTED;
-    if ((size_t)s->M * (size_t)s->Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
-    *need = (size_t)s->M * (size_t)s->Kg * (size_t)in_bytes(*in_t);
+    if ((size_t)s->M * (size_t)(s->Kg + 7) >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
+    *need = explicit_layout(*s, *in_t).total();
     return ICONV_OK;
 }
 
 // Lowering kernel into `workspace`, then the GEMM: a 1x1 stride-1 convolution over the lowered
-// matrix seen as a 1 x 1 x M image with Kg channels; the KRSC filter tensor already is the
-// K x Kg filter matrix in the same (tap-row, tap-column, channel) column order.
+// matrix seen as a 1 x 1 x M image with `pitch` channels; the KRSC filter tensor already is the
+// K x Kg filter matrix in the same (tap-row, tap-column, channel) column order (copied to the
+// padded pitch when the lowered rows are padded).
 int run_explicit(const void* x, const void* w, void* y, void* workspace, const ConvShape& s, int in_t, int out_t,
                  hipStream_t st) {
     drop_stale_error();
-    if (launch_im2col(x, workspace, s, in_bytes(in_t), st) != hipSuccess) return ICONV_ERR_LAUNCH;
+    const ExplicitLayout L = explicit_layout(s, in_t);
+    if (launch_im2col(x, workspace, s, in_bytes(in_t), L.pitch, st) != hipSuccess) return ICONV_ERR_LAUNCH;
+    const void* wg = w;
+    if (L.filter_bytes) {
+        void* wp = static_cast<char*>(workspace) + L.lowered_bytes;
+        if (launch_pad_rows(w, wp, s.K, s.Kg, L.pitch, st) != hipSuccess) return ICONV_ERR_LAUNCH;
+        wg = wp;
+    }
     ConvShape g;
-    g.N = 1; g.H = 1; g.W = s.M; g.C = s.Kg; g.K = s.K; g.R = 1; g.S = 1;
-    g.stride = 1; g.pad = 0; g.dil = 1; g.P = 1; g.Q = s.M; g.PQ = s.M; g.M = s.M; g.Kg = s.Kg;
-    return run_conv(workspace, w, y, g, in_t, out_t, -1, st);
+    g.N = 1; g.H = 1; g.W = s.M; g.C = L.pitch; g.K = s.K; g.R = 1; g.S = 1;
+    g.stride = 1; g.pad = 0; g.dil = 1; g.P = 1; g.Q = s.M; g.PQ = s.M; g.M = s.M; g.Kg = L.pitch;
+    return run_conv(workspace, wg, y, g, in_t, out_t, -1, st);
 }
 
 }  // namespace
@@ -186,7 +213,8 @@ size_t iconv_workspace_bytes(int algo, int N, int H, int W, int C, int K, int R,
     if (algo != ICONV_ALGO_EXPLICIT) return 0;
     if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK) return 0;
     if (!dtype_types(dtype, &in_t, &out_t)) return 0;
-    return (size_t)s.M * (size_t)s.Kg * (size_t)in_bytes(in_t);
+    if ((size_t)s.M * (size_t)(s.Kg + 7) >= (1ull << 31)) return 0;
+    return explicit_layout(s, in_t).total();
 }
 
 int iconv_im2col(const void* x, void* workspace, size_t workspace_bytes, int N, int H, int W, int C, int R, int S,
@@ -197,12 +225,12 @@ int iconv_im2col(const void* x, void* workspace, size_t workspace_bytes, int N, 
     if (rc != ICONV_OK) return rc;
     int in_t, out_t;
     if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
-    const size_t need = (size_t)s.M * (size_t)s.Kg * (size_t)in_bytes(in_t);
-    if ((size_t)s.M * (size_t)s.Kg >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < need) return ICONV_ERR_WORKSPACE;
+    if ((size_t)s.M * (size_t)(s.Kg + 7) >= (1ull << 31)) return ICONV_ERR_UNSUPPORTED;
+    const ExplicitLayout L = explicit_layout(s, in_t);
+    if (!workspace || workspace_bytes < L.lowered_bytes) return ICONV_ERR_WORKSPACE;
     if (!aligned16(x) || !aligned16(workspace)) return ICONV_ERR_ALIGN;
     drop_stale_error();
-    return status_of(launch_im2col(x, workspace, s, in_bytes(in_t), (hipStream_t)stream));
+    return status_of(launch_im2col(x, workspace, s, in_bytes(in_t), L.pitch, (hipStream_t)stream));
 }
 
 int iconv_fwd_explicit(const void* x, const void* w, void* y, void* workspace, size_t workspace_bytes, int N, int H,

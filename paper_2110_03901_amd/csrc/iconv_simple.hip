@@ -43,26 +43,73 @@ __global__ void __launch_bounds__(256) direct_kernel(const TI* __restrict__ x, c
 }
 
 // Explicit im2col (paper section 2.1): lowered[m][(r*S+s)*C + c], zero where the tap falls
-// outside the map.  One thread per VEC consecutive channels of one (m, tap).
-template <typename V, int VEC>
-__global__ void __launch_bounds__(256) im2col_kernel(const V* __restrict__ x, V* __restrict__ low, ConvShape s) {
-    const int cv = s.C / VEC;                       // vectors per pixel
-    const long long total = (long long)s.M * s.R * s.S * cv;
+// outside the map; rows are `pitch` elements long (Kg rounded up for the MFMA GEMM) and the tail
+// of a row is zero.  One thread per (output pixel, VEC-element piece of the channel run): it decodes
+// the pixel once and walks all R*S taps, so the index arithmetic is paid once per R*S pieces moved.
+// V: the piece type (16, 8, 4 or 2 bytes), cv pieces per pixel.
+template <typename V>
+__global__ void __launch_bounds__(256) im2col_kernel(const V* __restrict__ x, V* __restrict__ low, ConvShape s, int cv, int pitch_v) {
+    const long long total = (long long)s.M * cv;
     const long long stride_t = (long long)gridDim.x * blockDim.x;
+    const int RS = s.R * s.S;
     for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride_t) {
-        const int c = (int)(idx % cv);
-        long long t = idx / cv;
-        const int tap = (int)(t % (s.R * s.S));
-        const int m = (int)(t / (s.R * s.S));
-        const int r = tap / s.S, ss = tap - r * s.S;
+        const int m = (int)(idx / cv);
+        const int c = (int)(idx - (long long)m * cv);
         const int n = m / s.PQ;
         const int pq = m - n * s.PQ;
         const int p = pq / s.Q, q = pq - p * s.Q;
+        const int h0 = p * s.stride - s.pad, w0 = q * s.stride - s.pad;
+        const V* xn = x + (size_t)n * s.H * s.W * cv + c;
+        V* row = low + (size_t)m * pitch_v + c;
+        for (int r = 0; r < s.R; ++r) {
+            const int h = h0 + r * s.dil;
+            for (int ss = 0; ss < s.S; ++ss) {
+                const int ww = w0 + ss * s.dil;
+                V v = {};
+                if ((unsigned)h < (unsigned)s.H && (unsigned)ww < (unsigned)s.W) v = xn[((size_t)h * s.W + ww) * cv];
+                row[(size_t)(r * s.S + ss) * cv] = v;
+            }
+        }
+        // zero tail of the row (pitch beyond R*S*C), split over the pixel's threads
+        for (int t = RS * cv + c; t < pitch_v; t += cv) low[(size_t)m * pitch_v + t] = V{};
+    }
+}
+
+// The same for pixels of few pieces (cv < 4, e.g. four 16-bit channels = one 8-byte piece): one thread per
+// (output pixel, tap), taps fastest, so that the threads of a wave write one contiguous stretch of a lowered row.
+template <typename V>
+__global__ void __launch_bounds__(256) im2col_taps_kernel(const V* __restrict__ x, V* __restrict__ low, ConvShape s, int cv, int pitch_v) {
+    const int RS = s.R * s.S;
+    const int per_row = RS + (pitch_v - RS * cv + cv - 1) / cv;      // taps, then the zero tail in tap-sized steps
+    const long long total = (long long)s.M * per_row;
+    const long long stride_t = (long long)gridDim.x * blockDim.x;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride_t) {
+        const int m = (int)(idx / per_row);
+        const int tap = (int)(idx - (long long)m * per_row);
+        V* dst = low + (size_t)m * pitch_v + (size_t)tap * cv;
+        if (tap >= RS) {
+            for (int c = 0; c < cv && tap * cv + c < pitch_v; ++c) dst[c] = V{};
+            continue;
+        }
+        const int n = m / s.PQ;
+        const int pq = m - n * s.PQ;
+        const int p = pq / s.Q, q = pq - p * s.Q;
+        const int r = tap / s.S, ss = tap - r * s.S;
         const int h = p * s.stride - s.pad + r * s.dil, ww = q * s.stride - s.pad + ss * s.dil;
-        V v = {};
-        if ((unsigned)h < (unsigned)s.H && (unsigned)ww < (unsigned)s.W)
-            v = x[((size_t)((size_t)n * s.H + h) * s.W + ww) * cv + c];
-        low[idx] = v;
+        const bool ok = (unsigned)h < (unsigned)s.H && (unsigned)ww < (unsigned)s.W;
+        const V* src = x + ((size_t)((size_t)n * s.H + h) * s.W + ww) * cv;
+        for (int c = 0; c < cv; ++c) dst[c] = ok ? src[c] : V{};
+    }
+}
+
+// Filter matrix K x Kg copied into rows of `pitch` elements with a zero tail (the GEMM operand of the
+// explicit variant when Kg is not a multiple of eight elements).
+__global__ void __launch_bounds__(256) pad_rows_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, int rows,
+                                                      int len, int pitch) {
+    const long long total = (long long)rows * pitch;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / pitch), k = (int)(i - (long long)r * pitch);
+        dst[i] = k < len ? src[(size_t)r * len + k] : (uint16_t)0;
     }
 }
 
@@ -150,27 +197,37 @@ hipError_t launch_direct(const void* x, const void* w, void* y, const ConvShape&
     }
 }
 
-hipError_t launch_im2col(const void* x, void* low, const ConvShape& s, int elt_bytes, hipStream_t st) {
+hipError_t launch_im2col(const void* x, void* low, const ConvShape& s, int elt_bytes, int pitch_elems, hipStream_t st) {
     const int cbytes = s.C * elt_bytes;  // bytes of one pixel's channel run
-    if (cbytes % 16 == 0) {
-        const long long total = (long long)s.M * s.R * s.S * (cbytes / 16);
-        hipLaunchKernelGGL((im2col_kernel<uint4, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st, (const uint4*)x,
-                           (uint4*)low, ConvShape{s.N, s.H, s.W, cbytes / 16, s.K, s.R, s.S, s.stride, s.pad, s.dil,
-                                                  s.P, s.Q, s.M, s.PQ, s.Kg});
-    } else if (cbytes % 8 == 0) {
-        const long long total = (long long)s.M * s.R * s.S * (cbytes / 8);
-        hipLaunchKernelGGL((im2col_kernel<uint2, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st, (const uint2*)x,
-                           (uint2*)low, ConvShape{s.N, s.H, s.W, cbytes / 8, s.K, s.R, s.S, s.stride, s.pad, s.dil,
-                                                  s.P, s.Q, s.M, s.PQ, s.Kg});
-    } else if (elt_bytes == 4) {
-        const long long total = (long long)s.M * s.R * s.S * s.C;
-        hipLaunchKernelGGL((im2col_kernel<uint32_t, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st,
-                           (const uint32_t*)x, (uint32_t*)low, s);
-    } else {
-        const long long total = (long long)s.M * s.R * s.S * s.C;
-        hipLaunchKernelGGL((im2col_kernel<uint16_t, 1>), dim3(grid_for(total, 256)), dim3(256), 0, st,
-                           (const uint16_t*)x, (uint16_t*)low, s);
+    const long long pitch_bytes = (long long)pitch_elems * elt_bytes;
+    // the widest piece that divides both the channel run and the row pitch
+    int piece = 16;
+    while (piece > elt_bytes && ((cbytes % piece) != 0 || (pitch_bytes % piece) != 0)) piece >>= 1;
+    const int cv = cbytes / piece, pitch_v = (int)(pitch_bytes / piece);
+    if (cv < 4) {
+        const int RS = s.R * s.S;
+        const int grid = grid_for((long long)s.M * (RS + (pitch_v - RS * cv + cv - 1) / cv), 256);
+        switch (piece) {
+            case 16: hipLaunchKernelGGL(im2col_taps_kernel<uint4>, dim3(grid), dim3(256), 0, st, (const uint4*)x, (uint4*)low, s, cv, pitch_v); break;
+            case 8: hipLaunchKernelGGL(im2col_taps_kernel<uint2>, dim3(grid), dim3(256), 0, st, (const uint2*)x, (uint2*)low, s, cv, pitch_v); break;
+            case 4: hipLaunchKernelGGL(im2col_taps_kernel<uint32_t>, dim3(grid), dim3(256), 0, st, (const uint32_t*)x, (uint32_t*)low, s, cv, pitch_v); break;
+            default: hipLaunchKernelGGL(im2col_taps_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)low, s, cv, pitch_v); break;
+        }
+        return hipGetLastError();
     }
+    const int grid = grid_for((long long)s.M * cv, 256);
+    switch (piece) {
+        case 16: hipLaunchKernelGGL(im2col_kernel<uint4>, dim3(grid), dim3(256), 0, st, (const uint4*)x, (uint4*)low, s, cv, pitch_v); break;
+        case 8: hipLaunchKernelGGL(im2col_kernel<uint2>, dim3(grid), dim3(256), 0, st, (const uint2*)x, (uint2*)low, s, cv, pitch_v); break;
+        case 4: hipLaunchKernelGGL(im2col_kernel<uint32_t>, dim3(grid), dim3(256), 0, st, (const uint32_t*)x, (uint32_t*)low, s, cv, pitch_v); break;
+        default: hipLaunchKernelGGL(im2col_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)low, s, cv, pitch_v); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_rows(const void* src, void* dst, int rows, int len, int pitch, hipStream_t st) {
+    hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_for((long long)rows * pitch, 256)), dim3(256), 0, st, (const uint16_t*)src,
+                       (uint16_t*)dst, rows, len, pitch);
     return hipGetLastError();
 }
 

@@ -68,7 +68,13 @@ def test_workspace_bytes(lib):
     for L in workloads.LAYERS.values():
         code = 0 if L.dtype == "f32" else 1
         assert lib.iconv_workspace_bytes(0, *L.shape_args(), code) == 0          # implicit: none
-        assert lib.iconv_workspace_bytes(1, *L.shape_args(), code) == L.M * L.k_gemm * L.elt_bytes()
+        want = L.M * L.k_gemm * L.elt_bytes()                                    # the lowered matrix of section 2.1
+        if code != 0 and L.k_gemm % 8:
+            # 16-bit rows padded to a multiple of 8 elements, total rounded to 16 bytes, + the filter matrix at that pitch
+            pitch = (L.k_gemm + 7) // 8 * 8
+            want = (L.M * pitch * 2 + 15) // 16 * 16 + L.K * pitch * 2
+            assert L.name == "cfg5a" and pitch == 200
+        assert lib.iconv_workspace_bytes(1, *L.shape_args(), code) == want
     assert lib.iconv_workspace_bytes(1, 1, 2, 2, 1, 1, 3, 3, 1, 0, 1, 1) == 0    # invalid shape
 
 

@@ -355,6 +355,27 @@ def test_lowered_matrix_is_exact(B):
             assert np.array_equal(got[:, :, :, r, s, :], want)
 
 
+def test_lowered_matrix_rows_are_padded_for_the_matrix_cores(B):
+    """K_gemm = 3*3*4 = 36 is no multiple of 8: the lowered rows are 40 elements long with a zero tail, and
+    the explicit variant (which then multiplies with a padded copy of the filter matrix) still matches the oracle."""
+    L = workloads.small_layer("lowpad", 2, 9, 8, 4, 6, 3, 3, 1, 1, 1, seed_id=841)
+    x, _ = workloads.make_inputs(L)
+    xd = B.to_device(x, 1)
+    nbytes = B.iconv_workspace_bytes(B.ALGO_EXPLICIT, *L.shape_args(), 1)
+    assert nbytes == L.M * 40 * 2 + L.K * 40 * 2
+    ws = torch.full((nbytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    B.iconv_im2col(xd, ws, nbytes, L.N, L.H, L.W, L.C, L.R, L.S, L.stride, L.pad, L.dilation, 1)
+    torch.cuda.synchronize()
+    got = ws.float().cpu().numpy()[: L.M * 40].reshape(L.N, L.P, L.Q, 40)
+    assert np.array_equal(got[..., 36:], np.zeros_like(got[..., 36:]))
+    xp = np.zeros((L.N, L.H + 2, L.W + 2, L.C), np.float32)
+    xp[:, 1:-1, 1:-1] = x
+    for r in range(3):
+        for s_ in range(3):
+            assert np.array_equal(got[..., (r * 3 + s_) * 4:(r * 3 + s_) * 4 + 4], xp[:, r:r + L.P, s_:s_ + L.Q])
+    check(B, L, explicit=True)
+
+
 # ---- properties ------------------------------------------------------------------------------
 
 def test_runs_are_bit_identical(B):
