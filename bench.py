@@ -303,11 +303,18 @@ def main():
         a = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
         b = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
         t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3)
+        # LDS instruction cost: cycles per instruction and compute unit at the nominal 2.4 GHz
+        lds_iters = 2000
+        lds_cost = {}
+        for pi, pname in enumerate(B.LDS_PROBE_PATTERNS):
+            t_l = time_steps(lambda: B.iconv_probe_lds(pout, pout.numel() * 4, lds_iters, pi), 10, 2)
+            lds_cost[pname] = round(t_l * 1e-3 * 2.4e9 / (B.MFMA_PROBE_GROUPS / 256 * 4 * lds_iters * 8), 2)
         out["achievable"] = {"mfma_bf16_tflops": round(probe_tflops, 1),
                              "mfma_frac_of_datasheet": round(probe_tflops / PEAK_MFMA_TFLOPS, 4),
                              "mfma_bf16_tflops_random_operands": round(probe_random, 1),
                              "copy_gbs_read_plus_write": round(2 * nb / (t_c * 1e-3) / 1e9, 1),
-                             "value_frac_of_achievable_mfma": round(tflops / probe_tflops, 4)}
+                             "value_frac_of_achievable_mfma": round(tflops / probe_tflops, 4),
+                             "lds_cycles_per_b128_instruction_per_cu": lds_cost}
         del a, b, pout
         torch.cuda.empty_cache()
 
@@ -317,6 +324,11 @@ def main():
         b = torch.empty(n, dtype=torch.uint8, device="cuda:0")
         for _ in range(5):
             B.iconv_probe_copy(b, a, n)
+        # the LDS patterns with known conflicts, for reading SQ_LDS_BANK_CONFLICT
+        cal = torch.empty(B.MFMA_PROBE_GROUPS * 256, dtype=torch.float32, device="cuda:0")
+        for pi in range(len(B.LDS_PROBE_PATTERNS)):
+            for _ in range(3):
+                B.iconv_probe_lds(cal, cal.numel() * 4, 500, pi)
         torch.cuda.synchronize()
         out["calibration"] = {"copy_bytes_each_way": n, "launches": 5}
 

@@ -60,6 +60,33 @@ int iconv_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
  * away).  Returns ICONV_ERR_NULL, ICONV_ERR_SHAPE (iters < 1), ICONV_ERR_WORKSPACE (out too small). */
 int iconv_probe_mfma(void *out, size_t out_bytes, int iters, int random_operands, void *stream);
 
+/* A loop of `iters` x 8 LDS instructions per wave with one fixed 64-lane address pattern and nothing else, on
+ * the MFMA probe's grid (1024 workgroups of four waves, i.e. 128 * iters instructions per compute unit on 256
+ * compute units): what an LDS instruction costs, and what the bank-conflict counter reads for it.
+ *   pattern 0  ds_read_b128, lane l at byte 16 * l (conflict-free reference)
+ *   pattern 1  ds_write_b128, lane l at byte 16 * l
+ *   pattern 2  ds_read_b128 of the MFMA operand shape (lane l: tile row l % 32, 16-byte chunk l / 32) on
+ *              64-byte tile rows without a swizzle
+ *   pattern 3  the same through the kernels' swizzle of 64-byte rows
+ *   pattern 4  the same on 128-byte rows through the kernels' swizzle of 128-byte rows
+ *   pattern 5  ds_write_b128, the deposit of the kernels' output staging: 32 of the 64 lanes (16 pixels x 2
+ *              pieces) write 16-byte piece c of pixel i at iconv_lds_stage_offset(i, c)
+ *   pattern 6  the same with all 64 lanes (32 pixels), the deposit of the merged-tap kernel
+ *   pattern 7  as pattern 6 with piece c of pixel i at i * 128 + ((c ^ (i >> 1 & 7)) << 4): conflict-free as a
+ *              read, two lanes per bank in every pass as a write (reference for the counter)
+ * `out` as for iconv_probe_mfma.  Returns ICONV_ERR_UNSUPPORTED for another pattern, otherwise as
+ * iconv_probe_mfma. */
+int iconv_probe_lds(void *out, size_t out_bytes, int iters, int pattern, void *stream);
+
+/* The chunk position the MFMA kernels give 16-byte chunk `chunk` of tile row `row` in LDS rows of
+ * `chunks_per_row` (4 or 8) chunks - the very function the kernels compile, evaluated on the host, so that
+ * the layout can be checked against the bank model without a GPU.  Returns -1 for other arguments. */
+int iconv_lds_swizzle(int chunks_per_row, int row, int chunk);
+
+/* Byte offset of 16-byte piece `piece` (0..7) of pixel `pixel` in the kernels' output staging areas, again the
+ * function the kernels compile.  Returns -1 for a piece outside 0..7 or a negative pixel. */
+int iconv_lds_stage_offset(int pixel, int piece);
+
 #ifdef __cplusplus
 }
 #endif

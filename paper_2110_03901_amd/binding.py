@@ -47,6 +47,12 @@ _lib.iconv_probe_copy.restype = _i
 _lib.iconv_probe_copy.argtypes = [_p, _p, _sz, _p]
 _lib.iconv_probe_mfma.restype = _i
 _lib.iconv_probe_mfma.argtypes = [_p, _sz, _i, _i, _p]
+_lib.iconv_probe_lds.restype = _i
+_lib.iconv_probe_lds.argtypes = [_p, _sz, _i, _i, _p]
+_lib.iconv_lds_swizzle.restype = _i
+_lib.iconv_lds_swizzle.argtypes = [_i, _i, _i]
+_lib.iconv_lds_stage_offset.restype = _i
+_lib.iconv_lds_stage_offset.argtypes = [_i, _i]
 _lib.iconv_fwd_ex.restype = _i
 _lib.iconv_fwd_ex.argtypes = [_p, _p, _p] + [_i] * 13 + [_p]
 _lib.iconv_num_variants.restype = _i
@@ -64,7 +70,7 @@ NOALLOC_WORKSPACE_BYTES = 16 << 20
 EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit",
            "iconv_fwd_explicit_noalloc", "iconv_im2col",
            "iconv_kernel_for", "iconv_status_string"]
-EXPORTS_BENCH = ["iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy", "iconv_probe_mfma"]
+EXPORTS_BENCH = ["iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy", "iconv_probe_mfma", "iconv_probe_lds", "iconv_lds_swizzle", "iconv_lds_stage_offset"]
 
 
 class IconvError(RuntimeError):
@@ -181,6 +187,25 @@ def iconv_probe_mfma(out, out_bytes, iters, random_operands=False, stream=None) 
     rc = _lib.iconv_probe_mfma(_ptr(out), out_bytes, iters, int(bool(random_operands)), _stream(stream))
     if rc != 0:
         raise IconvError(rc)
+
+
+LDS_PROBE_PATTERNS = ("read_linear", "write_linear", "read_operand_rows64_unswizzled", "read_operand_rows64",
+                      "read_operand_rows128", "write_staging_deposit_16_pixels", "write_staging_deposit_32_pixels",
+                      "write_deposit_read_friendly_layout")
+
+
+def iconv_probe_lds(out, out_bytes, iters, pattern, stream=None) -> None:
+    rc = _lib.iconv_probe_lds(_ptr(out), out_bytes, iters, pattern, _stream(stream))
+    if rc != 0:
+        raise IconvError(rc)
+
+
+def iconv_lds_swizzle(chunks_per_row, row, chunk) -> int:
+    return _lib.iconv_lds_swizzle(chunks_per_row, row, chunk)
+
+
+def iconv_lds_stage_offset(pixel, piece) -> int:
+    return _lib.iconv_lds_stage_offset(pixel, piece)
 
 
 def iconv_num_variants() -> int:

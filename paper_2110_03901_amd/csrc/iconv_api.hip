@@ -279,6 +279,26 @@ int iconv_probe_mfma(void* out, size_t out_bytes, int iters, int random_operands
     return status_of(launch_mfma_probe(out, iters, random_operands != 0, (hipStream_t)stream));
 }
 
+int iconv_probe_lds(void* out, size_t out_bytes, int iters, int pattern, void* stream) {
+    if (!out) return ICONV_ERR_NULL;
+    if (iters < 1) return ICONV_ERR_SHAPE;
+    if (pattern < 0 || pattern >= kLdsProbePatterns) return ICONV_ERR_UNSUPPORTED;
+    if (out_bytes < (size_t)kMfmaProbeGroups * 256 * sizeof(float)) return ICONV_ERR_WORKSPACE;
+    if (!aligned16(out)) return ICONV_ERR_ALIGN;
+    drop_stale_error();
+    return status_of(launch_lds_probe(out, iters, pattern, (hipStream_t)stream));
+}
+
+int iconv_lds_stage_offset(int pixel, int piece) {
+    if (pixel < 0 || pixel >= (1 << 20) || piece < 0 || piece > 7) return -1;
+    return lds_stage_offset(pixel, piece);
+}
+
+int iconv_lds_swizzle(int chunks_per_row, int row, int chunk) {
+    if ((chunks_per_row != 4 && chunks_per_row != 8) || row < 0 || chunk < 0 || chunk >= chunks_per_row) return -1;
+    return lds_swizzle(chunks_per_row, row, chunk);
+}
+
 const char* iconv_kernel_for(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dilation, int dtype) {
     int in_t, out_t;
     ConvShape s;

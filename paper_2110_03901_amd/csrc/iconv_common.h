@@ -102,5 +102,9 @@ hipError_t launch_pad_rows(const void* src, void* dst, int rows, int len, int pi
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 constexpr int kMfmaProbeGroups = 1024;   // workgroups of the MFMA probe (four per compute unit)
 hipError_t launch_mfma_probe(void* out, int iters, bool random_operands, hipStream_t stream);
+constexpr int kLdsProbePatterns = 8;
+hipError_t launch_lds_probe(void* out, int iters, int pattern, hipStream_t stream);   // same grid and `out` as the MFMA probe
+int lds_swizzle(int chunks_per_row, int row, int chunk);
+int lds_stage_offset(int pixel, int piece);                // stage_off evaluated on the host   // swz<4> or swz<8> evaluated on the host
 
 }  // namespace iconv

@@ -18,7 +18,7 @@ constexpr int kRsrcFlags = 0x00020000;
 // bank window.  128-byte rows (and wider): XOR the row number, folded with row >> 3.  64-byte rows:
 // four consecutive rows fill a window, so the term must be constant over them and differ between
 // the four row quads of a pass (quads 0, 3, 5, 6 or 1, 2, 4, 7): the quad number's low two bits.
-template <int CPR> __device__ __forceinline__ int swz(int row, int chunk) {
+template <int CPR> __host__ __device__ __forceinline__ constexpr int swz(int row, int chunk) {
     if (CPR == 4) return chunk ^ ((row >> 2) & 3);
     constexpr int RP = (8 / CPR) > 0 ? (8 / CPR) : 1;  // tile rows per 128 bytes
     return chunk ^ (((row / RP) ^ (row >> 3)) & (CPR - 1));
@@ -125,13 +125,24 @@ template <> __device__ __forceinline__ void store_piece<f16_t>(u32x4 v, rsrc_t r
 // Bytes of wave-private LDS one call of store_frag_staged needs.
 constexpr int kFragStageBytes = 2048;
 
+// Output staging layout: byte offset of 16-byte piece `piece` (four filters, 0..7) of pixel `pixel` in a
+// staging area of 128-byte pixel rows.  The deposit is a ds_write_b128 in which eight consecutive lanes
+// hold the same piece of eight consecutive pixels, and the LDS serves a ds_write_b128 in passes of
+// eight consecutive lanes that must hit eight different 16-byte slots modulo 128 bytes (measured with
+// the bank-conflict counter on lane pairs): hence the xor with pixel % 8.  The read-back, lane l =
+// piece l%8 of pixel l/8 (+8, +16, ..), is a ds_read_b128, served in passes of 16 lanes (see swz above)
+// that must hit 16 different slots modulo 256 bytes; it does, two pixels x eight pieces per pass.
+__host__ __device__ __forceinline__ constexpr uint32_t stage_off(int pixel, int piece) {
+    return (uint32_t)(pixel * 128 + ((piece ^ (pixel & 7)) << 4));
+}
+
 // Writes one 32 x 32 accumulator fragment of the MFMA kernels to y through a wave-private LDS
 // staging area, so that every store instruction covers whole 128-byte lines of y rows.  In the
 // fragment lane l holds pixel l%32 and, in element v, filter 8*(v/4) + 4*(l/32) + v%4; written
 // directly, one store instruction would touch 32 rows with 32 bytes each.  Half a fragment (16
 // pixels x 32 filters, 2 KiB) goes through the staging area at a time: piece c (16 bytes, four
-// filters) of pixel i sits at i*128 + ((c ^ ((i >> 1) & 7)) << 4), which keeps both the deposit
-// (16 pixels x 2 pieces per instruction) and the row-wise read-back free of bank conflicts.  The
+// filters) of pixel i sits at stage_off(i, c), which keeps both the deposit (16 pixels x 2 pieces per
+// instruction) and the row-wise read-back free of bank conflicts.  The
 // read-back gives lane l piece l%8 of pixels l/8 and l/8 + 8 of the half: eight lanes = one line.
 // `row_off(i)` returns the byte offset, within the buffer of `y_rsrc`, of the first of the
 // fragment's 32 filters in the y row of fragment pixel i, or an offset that the piece offset
@@ -144,9 +155,9 @@ __device__ __forceinline__ void store_frag_staged(char* stg, const floatx16& acc
                                                   RowOff row_off) {
     const int frow = lane & 31, fk = lane >> 5, f16 = frow & 15;
     const int l8 = lane >> 3, c8 = lane & 7;
-    const uint32_t sw0 = (uint32_t)(f16 * 128 + ((fk ^ ((f16 >> 1) & 7)) << 4));         // piece 2*gq + fk: xor (gq << 5)
-    const uint32_t sr0 = (uint32_t)(l8 * 128 + ((c8 ^ ((l8 >> 1) & 7)) << 4));
-    const uint32_t sr1 = (uint32_t)((l8 + 8) * 128 + ((c8 ^ (((l8 + 8) >> 1) & 7)) << 4));
+    const uint32_t sw0 = stage_off(f16, fk);         // piece 2*gq + fk: xor (gq << 5)
+    const uint32_t sr0 = stage_off(l8, c8);
+    const uint32_t sr1 = stage_off(l8 + 8, c8);
     u32x4 out[2][2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {

@@ -216,13 +216,13 @@ ires_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     const uint32_t b_lane0 = (uint32_t)(f_lane * 64 + ((fk ^ ((f_lane >> 2) & 3)) << 4));
     const uint32_t b_lane1 = b_lane0 ^ 32u;
     // output staging, 16 pixels x 32 filters at a time: piece c (16 bytes, 4 filters) of pixel i at
-    // i*128 + ((c ^ ((i >> 1) & 7)) << 4)
+    // stage_off(i, c)
     char* stg = reinterpret_cast<char*>(lds) + g.w_bytes + g.NR * g.slice_bytes + wave * kResStage;
     const int f16 = frow & 15;
-    const uint32_t sw0 = (uint32_t)(f16 * 128 + ((fk ^ ((f16 >> 1) & 7)) << 4));        // piece 2*gq + fk: xor (gq << 5)
+    const uint32_t sw0 = stage_off(f16, fk);        // piece 2*gq + fk: xor (gq << 5)
     const int l8 = lane >> 3, c8 = lane & 7;
-    const uint32_t sr0 = (uint32_t)(l8 * 128 + ((c8 ^ ((l8 >> 1) & 7)) << 4));          // pixel l/8 (+8), piece l%8
-    const uint32_t sr1 = (uint32_t)((l8 + 8) * 128 + ((c8 ^ (((l8 + 8) >> 1) & 7)) << 4));
+    const uint32_t sr0 = stage_off(l8, c8);          // pixel l/8 (+8), piece l%8
+    const uint32_t sr1 = stage_off(l8 + 8, c8);
     const size_t y_elems = (size_t)s.M * s.K;
     const bool k_ok = nh * 32 + 4 * c8 + 3 < s.K;
 

@@ -1,6 +1,7 @@
-// Plain (non-MFMA) kernels: the direct convolution fallback, the explicit lowering kernel and
-// the copy probe.
+// Plain (non-MFMA) kernels: the direct convolution fallback, the explicit lowering kernels and
+// the copy, MFMA and LDS probes.
 #include "iconv_common.h"
+#include "iconv_device.h"
 
 namespace iconv {
 
@@ -158,6 +159,72 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* __restrict__ out
     out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
 }
 
+// LDS access-pattern probe: every wave issues `iters` x 8 ds_read_b128 (or ds_write_b128) of one fixed
+// 64-lane address pattern on a 6 KiB region of its own, nothing else in the loop.  Patterns:
+//   0  read, lane-linear (lane l at byte 16*l): the conflict-free reference
+//   1  write, lane-linear
+//   2  read, MFMA operand shape (lane l: tile row l%32, chunk l/32) on 64-byte rows, no swizzle
+//   3  the same through swz<4>, the layout of the kernels' 64-byte rows
+//   4  the same on 128-byte rows through swz<8>
+//   5  write, the deposit of store_frag_staged: lanes of 16 pixels (half the wave) write piece
+//      2*gq + l/32 of pixel l%16 at stage_off(pixel, piece), gq = 0..3
+//   6  write, the deposit of the merged-tap kernel: all 64 lanes, 32 pixels, the same layout
+//   7  write, 32 pixels, piece c of pixel i at i*128 + ((c ^ (i>>1 & 7)) << 4): a layout that is free of
+//      conflicts for reads but puts two lanes of every write pass on the same banks (reference)
+// Timed, it gives the cycles an LDS instruction costs a compute unit; under a counter pass it shows
+// what SQ_LDS_BANK_CONFLICT reads for accesses whose conflicts are known.
+template <int PATTERN>
+__global__ void __launch_bounds__(256) lds_probe_kernel(float* __restrict__ out, int iters) {
+    __shared__ u32x4 buf[4 * 384];
+    for (int i = threadIdx.x; i < 4 * 384; i += 256) buf[i] = u32x4{(uint32_t)i, 1u, 2u, 3u};
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = lane & 31, chunk = lane >> 5;
+    uint32_t byte;
+    if (PATTERN <= 1) byte = (uint32_t)lane * 16u;
+    else if (PATTERN == 2) byte = (uint32_t)(row * 64 + chunk * 16);
+    else if (PATTERN == 3) byte = (uint32_t)(row * 64 + swz<4>(row, chunk) * 16);
+    else if (PATTERN == 4) byte = (uint32_t)(row * 128 + swz<8>(row, chunk) * 16);
+    else if (PATTERN == 5) byte = stage_off(row & 15, chunk);
+    else if (PATTERN == 6) byte = stage_off(row, chunk);
+    else byte = (uint32_t)(row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+    // at most 31 * 128 + 7 * 16 + 16 bytes of pattern + 1792 bytes of instruction offsets = 5888 < 6144
+    const uint32_t addr = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)buf + (uint32_t)wave * 6144u + byte;
+    u32x4 sum = {0u, 0u, 0u, 0u};
+    for (int it = 0; it < iters; ++it) {
+        if (PATTERN >= 5) {
+            // pieces 2*gq + chunk: the address xor (gq << 5); two rounds, the second 2 KiB further on
+            const u32x4 v = {(uint32_t)it, (uint32_t)lane, 2u, 3u};
+            if (PATTERN >= 6 || row < 16)
+                asm volatile("ds_write_b128 %0, %4\n\tds_write_b128 %1, %4\n\tds_write_b128 %2, %4\n\tds_write_b128 %3, %4\n\t"
+                             "ds_write_b128 %0, %4 offset:2048\n\tds_write_b128 %1, %4 offset:2048\n\t"
+                             "ds_write_b128 %2, %4 offset:2048\n\tds_write_b128 %3, %4 offset:2048\n\ts_waitcnt lgkmcnt(0)"
+                             :
+                             : "v"(addr), "v"(addr ^ 32u), "v"(addr ^ 64u), "v"(addr ^ 96u), "v"(v)
+                             : "memory");
+        } else if (PATTERN == 1) {
+            const u32x4 v = {(uint32_t)it, (uint32_t)lane, 2u, 3u};
+            asm volatile("ds_write_b128 %0, %1\n\tds_write_b128 %0, %1 offset:256\n\tds_write_b128 %0, %1 offset:512\n\t"
+                         "ds_write_b128 %0, %1 offset:768\n\tds_write_b128 %0, %1 offset:1024\n\tds_write_b128 %0, %1 offset:1280\n\t"
+                         "ds_write_b128 %0, %1 offset:1536\n\tds_write_b128 %0, %1 offset:1792\n\ts_waitcnt lgkmcnt(0)"
+                         :
+                         : "v"(addr), "v"(v)
+                         : "memory");
+        } else {
+            u32x4 r0, r1, r2, r3, r4, r5, r6, r7;
+            asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:256\n\tds_read_b128 %2, %8 offset:512\n\t"
+                         "ds_read_b128 %3, %8 offset:768\n\tds_read_b128 %4, %8 offset:1024\n\tds_read_b128 %5, %8 offset:1280\n\t"
+                         "ds_read_b128 %6, %8 offset:1536\n\tds_read_b128 %7, %8 offset:1792\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3), "=&v"(r4), "=&v"(r5), "=&v"(r6), "=&v"(r7)
+                         : "v"(addr)
+                         : "memory");
+            sum ^= r0 ^ r1 ^ r2 ^ r3 ^ r4 ^ r5 ^ r6 ^ r7;
+        }
+    }
+    if (PATTERN == 1 || PATTERN >= 5) sum = buf[threadIdx.x];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = (float)(sum.x ^ sum.y ^ sum.z ^ sum.w);
+}
+
 int grid_for(long long total, int block) {
     long long g = (total + block - 1) / block;
     const long long cap = 256LL * 64;  // grid-stride beyond this
@@ -237,6 +304,28 @@ hipError_t launch_mfma_probe(void* out, int iters, bool random_operands, hipStre
     else
         hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(kMfmaProbeGroups), dim3(256), 0, st, (float*)out, iters);
     return hipGetLastError();
+}
+
+hipError_t launch_lds_probe(void* out, int iters, int pattern, hipStream_t st) {
+    const dim3 grid(kMfmaProbeGroups), block(256);
+    switch (pattern) {
+        case 0: hipLaunchKernelGGL(lds_probe_kernel<0>, grid, block, 0, st, (float*)out, iters); break;
+        case 1: hipLaunchKernelGGL(lds_probe_kernel<1>, grid, block, 0, st, (float*)out, iters); break;
+        case 2: hipLaunchKernelGGL(lds_probe_kernel<2>, grid, block, 0, st, (float*)out, iters); break;
+        case 3: hipLaunchKernelGGL(lds_probe_kernel<3>, grid, block, 0, st, (float*)out, iters); break;
+        case 4: hipLaunchKernelGGL(lds_probe_kernel<4>, grid, block, 0, st, (float*)out, iters); break;
+        case 5: hipLaunchKernelGGL(lds_probe_kernel<5>, grid, block, 0, st, (float*)out, iters); break;
+        case 6: hipLaunchKernelGGL(lds_probe_kernel<6>, grid, block, 0, st, (float*)out, iters); break;
+        case 7: hipLaunchKernelGGL(lds_probe_kernel<7>, grid, block, 0, st, (float*)out, iters); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+int lds_stage_offset(int pixel, int piece) { return (int)stage_off(pixel, piece); }
+
+int lds_swizzle(int chunks_per_row, int row, int chunk) {
+    return chunks_per_row == 4 ? swz<4>(row, chunk) : swz<8>(row, chunk);
 }
 
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {

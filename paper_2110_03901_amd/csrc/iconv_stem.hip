@@ -200,16 +200,15 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     // Output staging (vec_ok): each 32-pixel x 32-filter fragment goes through a 4 KiB area private
     // to the wave, so that 8 lanes store one pixel's 128 contiguous bytes (a whole cache line)
     // instead of 32 lanes storing 32 bytes of 32 different lines.  The 16-byte piece c of pixel t
-    // sits at piece c ^ ((t >> 1) & 7): both the deposit (16 lanes = 16 pixels, one piece) and the
-    // read-back (16 lanes = 2 pixels, 8 pieces) then cover all banks once.  LDS operations of one
-    // wave execute in order, so no wait is needed between deposit and read-back.
+    // sits at stage_off(t, c): neither the deposit (8 lanes of a write pass = 8 pixels, one piece) nor the
+    // read-back (16 lanes of a read pass = 2 pixels, 8 pieces) has a bank conflict.  LDS operations of
+    // one wave execute in order, so no wait is needed between deposit and read-back.
     char* stg = reinterpret_cast<char*>(lds) + g.b_bytes + 2 * g.patch_bytes + wave * 4096;
     const int c8 = lane & 7, l3 = lane >> 3;
-    uint32_t sw[4], sr[2];                        // deposit offset per filter quad; read-back offset, even/odd j
+    uint32_t sw[4];                               // deposit offset per filter quad
 #pragma unroll
-    for (int gq = 0; gq < 4; ++gq) sw[gq] = (uint32_t)(frow * 8 + ((2 * gq + fk) ^ ((frow >> 1) & 7))) * 16u;
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj) sr[jj] = (uint32_t)(l3 * 8 + (c8 ^ ((4 * jj + (lane >> 4)) & 7))) * 16u;
+    for (int gq = 0; gq < 4; ++gq) sw[gq] = stage_off(frow, 2 * gq + fk);
+    const uint32_t sr = stage_off(l3, c8);        // read-back: piece l%8 of pixel l/8 (+ 8j: 1024 bytes further on)
     // the lane's piece of pixel 8j + l/8 of fragment mi lies at y_lane + (a uniform offset of (mi, j))
     // bytes from the block's origin: 8j + l/8 < 32 <= 32 * (fragment index), and TW is 16 or 32
     const uint32_t y_lane = (uint32_t)(l3 * s.K + 4 * c8) * (uint32_t)sizeof(TO);
@@ -303,7 +302,7 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
                     }
                     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) out[mi][ni][j] = *reinterpret_cast<const u32x4*>(stg + sr[j & 1] + j * 1024);
+                    for (int j = 0; j < 4; ++j) out[mi][ni][j] = *reinterpret_cast<const u32x4*>(stg + sr + j * 1024);
                 }
             }
 #pragma unroll

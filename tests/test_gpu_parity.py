@@ -436,6 +436,37 @@ def test_probes_run_and_are_exact(B):
         B.iconv_probe_mfma(out, 16, 1)
 
 
+def test_lds_probe_reads_what_its_pattern_says(B):
+    """One iteration of the LDS probe: every lane xors the eight 16-byte words its pattern addresses (word i of
+    the buffer holds i in its first element, the wave's region starts at word 384 * wave), so the output pins
+    the address pattern, the kernels' swizzle included."""
+    out = torch.empty(B.MFMA_PROBE_GROUPS * 256, dtype=torch.float32, device="cuda:0")
+    lane = np.arange(64)
+    row, chunk = lane & 31, lane >> 5
+    words = {0: lane,
+             2: row * 4 + chunk,
+             3: row * 4 + np.array([B.iconv_lds_swizzle(4, int(r), int(c)) for r, c in zip(row, chunk)]),
+             4: row * 8 + np.array([B.iconv_lds_swizzle(8, int(r), int(c)) for r, c in zip(row, chunk)])}
+    for pattern, word in words.items():
+        out.fill_(float("nan"))
+        B.iconv_probe_lds(out, out.numel() * 4, 1, pattern)
+        torch.cuda.synchronize()
+        want = np.zeros((4, 64), dtype=np.int64)
+        for wave in range(4):
+            for k in range(8):
+                want[wave] ^= 384 * wave + word + 16 * k
+        got = out.view(-1, 4, 64).cpu().numpy()
+        assert np.array_equal(got, np.broadcast_to(want.astype(np.float32), got.shape)), pattern
+    for pattern in (1, 5, 6, 7):                             # the write patterns: run, leave numbers
+        B.iconv_probe_lds(out, out.numel() * 4, 3, pattern)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all())
+    with pytest.raises(B.IconvError):
+        B.iconv_probe_lds(out, out.numel() * 4, 1, len(B.LDS_PROBE_PATTERNS))
+    with pytest.raises(B.IconvError):
+        B.iconv_probe_lds(out, 16, 1, 0)
+
+
 CHANNEL_LAST = ["tile_tail", "c24_partial_chunk", "c72_k130", "stride2", "stride3_dil2", "dil2_pad2", "big_pad",
                 "one_by_one_s2", "p1_q1", "r5s3", "seven_by_seven", "single_pixel", "direct_c3", "stem_c4"]
 

@@ -1,0 +1,171 @@
+"""CPU checks of the LDS layouts of the MFMA kernels against a bank model of gfx950.
+
+The model (measured on the chip by timing ds_read_b128 of lane pairs that share a bank, and by timing whole
+patterns): the 64 lanes of a ds_read_b128 are served in four passes of 16 lanes - lanes {0-3, 12-15, 20-27},
+{4-11, 16-19, 28-31} and the same two sets + 32 - and a pass takes as many turns as the most loaded 16-byte
+slot of the 256-byte bank window (64 banks x 4 bytes) has DIFFERENT addresses in it.  Four turns per
+instruction is conflict-free.  A ds_write_b128 is served in eight passes of eight CONSECUTIVE lanes
+(measured with the bank-conflict counter on lane pairs), inactive lanes included, and a pass takes as many
+turns as its most loaded 16-byte slot modulo 128 bytes has different addresses: eight turns per instruction
+is conflict-free.
+
+The swizzle of the per-tap and patch kernels' tile rows and the layout of the output staging areas are
+taken from the library itself (iconv_lds_swizzle and iconv_lds_stage_offset evaluate the functions the
+kernels compile, on the host); the operand address formulas of the resident-filter kernels are restated
+here from csrc/iconv_resident.hip and csrc/iconv_rowres.hip, and the lane-to-(pixel, piece) assignment of
+the staging accesses from csrc/iconv_device.h (store_frag_staged) and csrc/iconv_stem.hip, for the geometry
+of the headline layer.  No GPU is needed.
+"""
+import ctypes
+import os
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2110_03901_amd", "libiconv_mi355.so")
+
+PASSES = [[0, 1, 2, 3, 12, 13, 14, 15, 20, 21, 22, 23, 24, 25, 26, 27],
+          [4, 5, 6, 7, 8, 9, 10, 11, 16, 17, 18, 19, 28, 29, 30, 31]]
+PASSES += [[l + 32 for l in p] for p in list(PASSES)]
+
+
+def turns(addr):
+    """LDS turns of one ds_read_b128 whose lane l reads 16 bytes at byte address addr[l] (4 = conflict-free)."""
+    assert len(addr) == 64 and all(a % 16 == 0 for a in addr)
+    total = 0
+    for lanes in PASSES:
+        slots = {}
+        for l in lanes:
+            slots.setdefault((addr[l] >> 4) & 15, set()).add(addr[l])
+        total += max(len(v) for v in slots.values())
+    return total
+
+
+def write_turns(addr):
+    """LDS turns of one ds_write_b128; addr[l] is None for an inactive lane (8 = conflict-free)."""
+    total = 0
+    for p in range(8):
+        slots = {}
+        for l in range(8 * p, 8 * p + 8):
+            if addr[l] is not None:
+                slots.setdefault((addr[l] >> 4) & 7, set()).add(addr[l])
+        total += max([len(v) for v in slots.values()] + [1])
+    return total
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.skip("library not built")
+    h = ctypes.CDLL(LIB)
+    h.iconv_lds_swizzle.restype = ctypes.c_int
+    h.iconv_lds_swizzle.argtypes = [ctypes.c_int] * 3
+    h.iconv_lds_stage_offset.restype = ctypes.c_int
+    h.iconv_lds_stage_offset.argtypes = [ctypes.c_int] * 2
+    return h
+
+
+def test_model_tells_layouts_apart():
+    """The model is not vacuous: lane-linear reads are free, unswizzled 64-byte operand rows are 8-way
+    conflicted, and the earlier swizzle of 64-byte rows, free of conflicts for plain quarter-waves, is 2-way
+    conflicted for the real lane sets (what the timing showed, and why it was replaced)."""
+    assert turns([16 * l for l in range(64)]) == 4
+    assert turns([(l & 31) * 64 + (l >> 5) * 16 for l in range(64)]) == 16
+    old = lambda row, c: c ^ (((row >> 1) ^ (row >> 3)) & 3)
+    assert turns([(l & 31) * 64 + old(l & 31, l >> 5) * 16 for l in range(64)]) == 8
+    quarter = [list(range(16 * i, 16 * i + 16)) for i in range(4)]
+    addr = [(l & 31) * 64 + old(l & 31, l >> 5) * 16 for l in range(64)]
+    assert all(len({(addr[l] >> 4) & 15 for l in q}) == 16 for q in quarter)
+
+
+@pytest.mark.parametrize("cpr", [4, 8])
+def test_tile_row_swizzle_is_a_permutation_and_conflict_free(lib, cpr):
+    """swz<CPR>: chunks of a row stay in the row (so the lane-linear LDS-DMA fill can apply it on the global
+    side), and the operand read of every fragment (32 consecutive rows from a multiple of 32, chunk
+    2*kk + l/32 for K slice kk) is conflict-free."""
+    for row in range(512):
+        assert sorted(lib.iconv_lds_swizzle(cpr, row, c) for c in range(cpr)) == list(range(cpr))
+    for base in range(0, 512, 32):
+        for kk in range(cpr // 2):
+            addr = [((base + (l & 31)) * cpr + lib.iconv_lds_swizzle(cpr, base + (l & 31), 2 * kk + (l >> 5))) * 16
+                    for l in range(64)]
+            assert turns(addr) == 4, (cpr, base, kk)
+    assert lib.iconv_lds_swizzle(4, 0, 4) == -1 and lib.iconv_lds_swizzle(6, 0, 0) == -1
+
+
+def resident_operand(TW, PWp, MF, S, cpr, sws, skew, stride=1, dil=1):
+    """Byte addresses of every pixel-operand read of the resident-filter kernels' K loop (filter row 0; a row
+    further down adds dil * PWp rows, a multiple of 16, and flips the skew bit with the parity of r * dil for all
+    lanes alike): fragment mf of pixel half m_half, tap column sc, K slice kk."""
+    RB = cpr * 16
+    swb = 3 if cpr == 8 else 2
+    for m_half in range(2):
+        for mf in range(MF):
+            for sc in range(S):
+                for kk in range(cpr // 2):
+                    for rpar in range(2):                      # parity of r * dil
+                        addr = []
+                        for l in range(64):
+                            frow, fk = l & 31, l >> 5
+                            t = (m_half * MF + mf) * 32 + frow
+                            th, tw = divmod(t, TW)
+                            pix = (th * PWp + tw) * stride + sc * dil
+                            odd = (skew & th & 1) << (swb - 1)
+                            a = pix * RB + ((fk ^ ((pix >> sws) & (cpr - 1)) ^ odd) << 4)
+                            a ^= kk << 5
+                            a ^= (skew & rpar) * (16 << (swb - 1))
+                            addr.append(a)
+                        yield (m_half, mf, sc, kk, rpar), addr
+
+
+def test_resident_filter_operand_reads_headline_geometry():
+    """cfg2 (56-pixel block rows in 64-pixel patch rows): with the skew of odd patch rows every pixel-operand
+    read is conflict-free in both forms of the kernel; without it the fragments that run on into the next
+    block row are 2-way conflicted (the reason the skew exists)."""
+    # channel-slice form: 64-byte rows of 32 channels, swizzle (i >> 2) & 3
+    for key, addr in resident_operand(56, 64, 7, 3, 4, 2, skew=1):
+        assert turns(addr) == 4, ("slice form", key)
+    # row-phased form: 128-byte rows of 64 channels, swizzle (i >> 1) & 7; and 64-byte rows for 32 channels
+    for key, addr in resident_operand(56, 64, 7, 3, 8, 1, skew=1):
+        assert turns(addr) == 4, ("row form, 64 channels", key)
+    for key, addr in resident_operand(56, 64, 7, 3, 4, 2, skew=1):
+        assert turns(addr) == 4, ("row form, 32 channels", key)
+    worst = max(turns(addr) for _, addr in resident_operand(56, 64, 7, 3, 4, 2, skew=0))
+    assert worst == 8
+
+
+@pytest.mark.parametrize("cpr,sws", [(4, 2), (8, 1)])
+def test_resident_filter_filter_reads(cpr, sws):
+    """Filter fragment of (tap, K slice kk): filter 32*nh + l%32, chunk 2*kk + l/32 of rows of cpr chunks."""
+    RB = cpr * 16
+    for nh in range(2):
+        for kk in range(cpr // 2):
+            addr = []
+            for l in range(64):
+                f = nh * 32 + (l & 31)
+                addr.append((f * RB + (((l >> 5) ^ ((f >> sws) & (cpr - 1))) << 4)) ^ (kk << 5))
+            assert turns(addr) == 4, (nh, kk)
+
+
+def test_output_staging(lib):
+    """Output staging of every MFMA kernel (piece c of pixel i at iconv_lds_stage_offset(i, c)).
+    store_frag_staged: the lanes of 16 pixels deposit piece 2*gq + l/32 of pixel l%16, gq = 0..3, then lane l
+    reads back piece l%8 of pixels l/8 and l/8 + 8.  Merged-tap kernel: all 64 lanes deposit (32 pixels), then
+    four read-backs of pixels l/8 + 8j.  No access has a bank conflict, every piece has a place of its own, and
+    the layout it replaced - free of conflicts for reads - put two lanes of every write pass on the same banks
+    (what the counter showed)."""
+    off = lib.iconv_lds_stage_offset
+    assert off(0, 8) == -1 and off(-1, 0) == -1
+    assert len({off(i, c) for i in range(32) for c in range(8)}) == 256
+    assert all(off(i, c) // 128 == i and off(i, c) % 16 == 0 for i in range(32) for c in range(8))
+    for plus in (0, 8, 16, 24):
+        assert turns([off((l >> 3) + plus, l & 7) for l in range(64)]) == 4
+    for gq in range(4):
+        for h in range(2):
+            half = [off(l & 15, 2 * gq + (l >> 5)) if ((l & 31) >> 4) == h else None for l in range(64)]
+            assert write_turns(half) == 8
+        assert write_turns([off(l & 31, 2 * gq + (l >> 5)) for l in range(64)]) == 8
+    old = lambda i, c: i * 128 + ((c ^ ((i >> 1) & 7)) << 4)
+    assert turns([old(l >> 3, l & 7) for l in range(64)]) == 4
+    assert write_turns([old(l & 31, l >> 5) for l in range(64)]) == 16
+    assert write_turns([16 * l for l in range(64)]) == 8
