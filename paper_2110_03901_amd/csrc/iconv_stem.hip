@@ -27,7 +27,8 @@ namespace {
 
 struct StemGeom {
     int TH, TW_LOG2;     // output block: TH rows, TW = 1 << TW_LOG2 (16 or 32) columns
-    int PH, PPAIRS;      // patch rows, 16-byte pixel pairs per patch row
+    int PH, PPAIRS;      // patch rows, 16-byte pixel pairs per patch row (the row pitch)
+    int PPAIRS_USED;     // pairs of a patch row that hold pixels; the rest is padding that is never read
     int tiles_h, tiles_w, tiles_n;
     int total_tiles;
     int tiles_base, tiles_rem;   // workgroup i owns tiles_base (+1 if i < tiles_rem) consecutive blocks
@@ -87,8 +88,9 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     for (int i = 0; i < kStemPatchItems; ++i) {
         const int pi = i * (kStemWaves * 64) + tid;
         const int ph = (int)(((float)pi + 0.5f) * g.inv_ppairs);
-        p_h[i] = pi < npairs ? ph : 0;
-        p_w[i] = pi < npairs ? 2 * (pi - ph * g.PPAIRS) : -(1 << 30);
+        const bool used = pi < npairs && pi - ph * g.PPAIRS < g.PPAIRS_USED;
+        p_h[i] = used ? ph : 0;
+        p_w[i] = used ? 2 * (pi - ph * g.PPAIRS) : -(1 << 30);
     }
     auto load_patch = [&](int tile, u32x4 (&regs)[kStemPatchItems]) {
         const StemTile tc = stem_decode(tile, g);
@@ -361,13 +363,18 @@ bool plan_stem(const ConvShape& s, StemGeom* g) {
     int TH = BM / TW;
     if (TH > s.P) TH = s.P;
     const int PH = (TH - 1) * s.stride + s.R;
-    const int ppairs = ((TW - 1) * s.stride + 8) / 2;
+    const int ppairs_used = ((TW - 1) * s.stride + 8) / 2;
+    // A fragment of 32 pixels is two block rows when TW = 16.  Its operand read is free of bank conflicts
+    // when the second row starts a multiple of 16 pairs (256 bytes) after the first: the two halves of a
+    // 16-lane pass (columns 0-3, 12-15 of one row, 4-11 of the other) then share a bank window without
+    // overlapping.  Block rows are `stride` patch rows apart, so the pitch is padded to a multiple of 8.
+    const int ppairs = tw_log2 == 4 ? (ppairs_used + 7) / 8 * 8 : ppairs_used;
     const long patch_bytes = (((long)PH * ppairs + 255) / 256) * 4096;   // whole workgroup-wide pieces
     if (patch_bytes > kStemPatchItems * 4096) return false;
     const long b_bytes = (long)s.R * 4 * kStemBN * 16;
     if (2 * patch_bytes + b_bytes + kStemStageBytes > kStemLdsLimit) return false;
     if ((long)TH * s.Q * s.K * 4 >= (1L << 31)) return false;            // in-block output offsets are 32-bit
-    g->TH = TH; g->TW_LOG2 = tw_log2; g->PH = PH; g->PPAIRS = ppairs;
+    g->TH = TH; g->TW_LOG2 = tw_log2; g->PH = PH; g->PPAIRS = ppairs; g->PPAIRS_USED = ppairs_used;
     g->tiles_h = (s.P + TH - 1) / TH; g->tiles_w = (s.Q + TW - 1) / TW; g->tiles_n = (s.K + kStemBN - 1) / kStemBN;
     g->shift = shift; g->b_bytes = (int)b_bytes; g->patch_bytes = (int)patch_bytes; g->inv_ppairs = 1.0f / (float)ppairs;
     const long total = (long)s.N * g->tiles_h * g->tiles_w * g->tiles_n;

@@ -169,3 +169,25 @@ def test_output_staging(lib):
     assert turns([old(l >> 3, l & 7) for l in range(64)]) == 4
     assert write_turns([old(l & 31, l >> 5) for l in range(64)]) == 16
     assert write_turns([16 * l for l in range(64)]) == 8
+
+
+def test_merged_tap_kernel_patch_reads():
+    """csrc/iconv_stem.hip: the patch holds 16-byte pixel pairs, row pitch PPAIRS pairs; lane l of fragment f reads
+    the pair at (th * stride * PPAIRS + tw * stride / 2 + l/32) of block pixel t = 32 f + l%32 (th = t / TW,
+    tw = t % TW), plus offsets that are the same for all lanes.  With 16-pixel block rows a fragment spans two block
+    rows, which is conflict-free for a pitch that is a multiple of 8 pairs (what the host plans: 19 used pairs
+    padded to 24 for the 7x7 stride-2 stem) and was 2-way conflicted at the unpadded pitch; 32-pixel block rows
+    need no padding."""
+    def reads(tw_log2, ppairs, stride=2):
+        TW = 1 << tw_log2
+        for frag in range(8):
+            for fk_extra in (0, 2):                # K slice kk: + 2 pairs
+                addr = []
+                for l in range(64):
+                    t = frag * 32 + (l & 31)
+                    th, tw = t >> tw_log2, t & (TW - 1)
+                    addr.append((th * stride * ppairs + tw * (stride >> 1) + (l >> 5) + fk_extra) * 16)
+                yield addr
+    assert all(turns(a) == 4 for a in reads(4, 24))
+    assert max(turns(a) for a in reads(4, 19)) > 4
+    assert all(turns(a) == 4 for a in reads(5, 35))
