@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libiconv_mi355.so")
-SOURCES = ["iconv_api.hip", "iconv_simple.hip", "iconv_mfma.hip", "iconv_patch.hip", "iconv_stem.hip", "iconv_resident.hip", "iconv_rowres.hip", "iconv_chlast.hip"]
+SOURCES = ["iconv_api.hip", "iconv_simple.hip", "iconv_mfma.hip", "iconv_patch.hip", "iconv_stem.hip", "iconv_resident.hip", "iconv_rowres.hip", "iconv_pointwise.hip", "iconv_chlast.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

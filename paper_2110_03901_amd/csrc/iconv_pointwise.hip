@@ -1,0 +1,324 @@
+// 1x1 convolutions (any stride): the pixel-resident kernel.
+//
+// A 1x1 layer is the GEMM  y[M x K] = x'[M x C] * w[K x C]^T  whose rows are the (sampled) input pixels
+// themselves: the per-tap decomposition of the paper (section 3.2) with a single tap.  Its cost on
+// this chip is the write of y, so the kernel is built around keeping the stores going:
+//
+//  * a workgroup owns up to 128 consecutive output pixels; their C channels are loaded into LDS once
+//    (the "A" operand stays resident) and the filters stream through a ring of eight slots in tiles of 32
+//    (eight loader waves -- a wave gets out only one global -> LDS load per 130-200 ns -- three tiles ahead: a tile takes about a microsecond to
+//    arrive from L2 under load, several times what multiplying it takes);
+//  * two TEAMS of four compute waves take the filter tiles in turn.  Time is cut into ticks by one
+//    workgroup barrier per filter tile: in tick k team k%2 multiplies tile k (four waves, 32 pixels x
+//    32 filters each; a wave reads the fragments of its 32 pixels from LDS once and keeps them in
+//    registers for all tiles, so a K step is one filter-fragment read and one MFMA), the other team
+//    writes out tile k-1 from
+//    its accumulators, and the loader waves request tile k+3 into the slot tile k-1 has left.  So
+//    from the second tick on stores, MFMAs and loads overlap, which a one-tile-per-workgroup kernel
+//    cannot do.
+//
+// LDS: [pixels: 128 rows x 2C bytes][filters: 4 slots x 32 rows x 2C bytes][staging: 2 KiB per compute
+// wave]; once the pixel fragments are in registers the pixel region serves as four more filter slots.
+// Rows hold their 16-byte chunks XOR-swizzled so that the MFMA operand read (32 consecutive
+// rows, one chunk per half-wave) is free of bank conflicts: rows of 256 bytes and more xor the low four
+// chunk bits with row % 16, 128-byte rows use swz<8>.  The DMA fills write lane-linear and apply the
+// swizzle on the global side.
+#include <atomic>
+
+#include "iconv_common.h"
+#include "iconv_device.h"
+#include "iconv_host.h"
+
+namespace iconv {
+
+namespace {
+
+constexpr int kPwBM = 128;        // pixels per workgroup at most
+constexpr int kPwBN = 32;         // filters per tile
+constexpr int kPwSlots = 8;       // filter tiles in LDS: a pair in use, up to three pairs landing
+constexpr int kPwWaves = 16;      // 2 teams x 4 compute waves + 8 loader waves
+constexpr int kPwLoaders = 8;
+constexpr int kPwStage = kFragStageBytes;
+constexpr uint32_t kPwDrop = 0x80000000u;   // offset that every buffer of this kernel treats as out of range
+
+struct PwGeom {
+    int rows_per_wg;     // output pixels per workgroup (<= 128)
+    int tiles_n;         // filter tiles of 32
+    float inv_q, inv_p;  // 1 / Q, 1 / P
+};
+
+// chunk position of 16-byte chunk c of LDS row `row` (rows of CPR chunks)
+template <int CPR> __host__ __device__ __forceinline__ constexpr int pw_swz(int row, int c) {
+    return CPR >= 16 ? (c ^ (row & 15)) : swz<8>(row, c);
+}
+
+// Byte offset in LDS of filter-tile slot s (0..7).  Slots 0-3 follow the pixel region; slots 4-7 ARE the pixel
+// region, which is free once every compute wave has taken its pixel fragments into registers.
+template <int CPR> __device__ __forceinline__ uint32_t pw_slot(int s) {
+    constexpr uint32_t A_BYTES = kPwBM * CPR * 16, B_BYTES = kPwBN * CPR * 16;
+    static_assert(4 * B_BYTES <= A_BYTES, "four tiles fit the pixel region");
+    return s < 4 ? A_BYTES + (uint32_t)s * B_BYTES : (uint32_t)(s - 4) * B_BYTES;
+}
+
+template <typename T, typename TO, int CPR>
+__global__ void __launch_bounds__(kPwWaves * 64)
+ipw_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const PwGeom g) {
+    static_assert(CPR == 8 || CPR == 16 || CPR == 32, "64, 128 or 256 channels");
+    typedef typename Elem<T>::frag frag_t;
+    constexpr int PITCH = CPR * 16;             // bytes of an LDS row (all channels of a pixel or filter)
+    constexpr int RPI = 64 / CPR;               // rows one wave-wide DMA instruction fills
+    constexpr int NA = kPwBM / RPI;             // instructions for the pixel rows
+    constexpr int NB = kPwBN / RPI;             // instructions for one filter tile
+    constexpr int KK = CPR / 2;                 // K slices of 16 channels
+    constexpr int A_BYTES = kPwBM * PITCH, B_BYTES = kPwBN * PITCH;
+    constexpr int LPT = (NB + kPwLoaders - 1) / kPwLoaders;     // loads per loader wave and filter tile
+
+    extern __shared__ u32x4 lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)lds;
+
+    const int m0 = blockIdx.x * g.rows_per_wg;
+    const int rows = min(g.rows_per_wg, s.M - m0);          // >= 1 by construction of the grid
+    // first pixel of the workgroup, decoded once
+    const int n0 = m0 / s.PQ;
+    const int rem0 = m0 - n0 * s.PQ;
+    const int p0 = rem0 / s.Q;
+    const int q0 = rem0 - p0 * s.Q;
+
+    // ---- buffers.  x is addressed from the start of image n0: the at most 128 pixels of the workgroup
+    // lie in a few consecutive images, whose bytes the host has checked to stay below 2^31.
+    const size_t x_off = (size_t)n0 * s.H * s.W * s.C;
+    const size_t x_rem = ((size_t)s.N * s.H * s.W * s.C - x_off) * 2u;
+    const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x) + x_off, 0, x_rem > kPwDrop ? kPwDrop : (uint32_t)x_rem,
+                                                           kRsrcFlags);
+    const uint32_t w_bytes = (uint32_t)s.K * s.C * 2u;      // < 2^31 (host)
+    const rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(w), 0, w_bytes, kRsrcFlags);
+
+    const int r_in = lane / CPR, pc = lane % CPR;           // row within an instruction, physical chunk
+    // global byte offset of the lane's chunk of pixel row `row` (0..127) of the workgroup, or kPwDrop
+    auto a_offset = [&](int row) -> uint32_t {
+        const int lc = pw_swz<CPR>(row, pc);                // the swizzle is an involution on the chunk number
+        const int qq = q0 + row;
+        const int dp = (int)(((float)qq + 0.5f) * g.inv_q);     // exact: qq < Q + 128, Q < 2^14 (host)
+        const int q = qq - dp * s.Q;
+        const int pp = p0 + dp;
+        const int dn = (int)(((float)pp + 0.5f) * g.inv_p);
+        const int p = pp - dn * s.P;
+        const int h = p * s.stride - s.pad, ww = q * s.stride - s.pad;
+        const bool ok = row < rows && (unsigned)h < (unsigned)s.H && (unsigned)ww < (unsigned)s.W;
+        return ok ? (uint32_t)(((dn * s.H + h) * s.W + ww) * s.C + lc * 8) * 2u : kPwDrop;
+    };
+    // global byte offset of the lane's chunk of filter row `row` (0..63) of filter tile `tile`
+    auto b_offset = [&](int tile, int row) -> uint32_t {
+        const int lc = pw_swz<CPR>(row, pc);
+        const int k = tile * kPwBN + row;
+        return k < s.K ? (uint32_t)(k * s.C + lc * 8) * 2u : kPwDrop;
+    };
+
+    // ---- phase 0: the pixels and filter tiles 0 and 1, one share per wave (all sixteen issue)
+#pragma unroll
+    for (int i = 0; i < (NA + 2 * NB + kPwWaves - 1) / kPwWaves; ++i) {
+        const int j = wave + i * kPwWaves;                  // uniform
+        if (j < NA) {
+            dma16(x_rsrc, a_offset(j * RPI + r_in), lds_base + (uint32_t)j * 1024u);
+        } else if (j < NA + 2 * NB) {
+            const int jb = j - NA;                          // tile jb / NB, instruction jb % NB of it
+            dma16(w_rsrc, b_offset(jb / NB, (jb % NB) * RPI + r_in), lds_base + A_BYTES + (uint32_t)jb * 1024u);
+        }
+    }
+
+    const int NT = g.tiles_n;
+    const int NP = (NT + 1) / 2;                            // ticks: pairs of filter tiles
+    if (wave >= 8) {
+        // =========================== loader waves ===========================================
+        const int lw = wave - 8;
+        auto request = [&](int tile) {                      // this wave's loads of filter tile `tile`, if there is one
+            if (tile >= NT) return;
+            const uint32_t slot = lds_base + pw_slot<CPR>(tile & (kPwSlots - 1));
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int j = lw + i * kPwLoaders;          // uniform
+                if (j < NB) dma16(w_rsrc, b_offset(tile, j * RPI + r_in), slot + (uint32_t)j * 1024u);
+            }
+        };
+        // Loads complete in order within a wave: once at most the loads of the `after` tiles requested last are
+        // outstanding, everything requested before them has landed.
+        const bool issues = lw < NB;                        // with few loads per tile some loader waves have none
+        auto landed_but = [&](int after) {
+            if (!issues || after <= 0) wait_vmcnt<0>();
+            else if (after == 1) wait_vmcnt<LPT>();
+            else if (after == 2) wait_vmcnt<2 * LPT>();
+            else if (after == 3) wait_vmcnt<3 * LPT>();
+            else wait_vmcnt<4 * LPT>();
+        };
+        auto tiles_in = [&](int first, int last) { return max(0, min(NT - 1, last) - first + 1); };   // existing tiles of a range
+        request(2);
+        request(3);
+        landed_but(tiles_in(2, 3));                         // phase 0 (pixels, tiles 0 and 1) is in LDS
+        __syncthreads();
+        for (int j = 0; j < NP; ++j) {
+            // Tick j works on pair j (tiles 2j, 2j+1); pair j+1 must have landed when it ends.  Pairs up to j+3 may
+            // be in flight: pair j+3 takes the slots of pair j-1, which every wave has left at the last barrier.
+            // Nothing is requested in tick 0: pairs 2 and 3 go to the pixel region, which is read during tick 0.
+            if (j == 1) {
+                for (int t = 4; t < 10; ++t) request(t);
+            } else if (j >= 2) {
+                request(2 * j + 6);
+                request(2 * j + 7);
+            }
+            landed_but(j == 0 ? 0 : tiles_in(2 * j + 4, 2 * j + 7));
+            __syncthreads();
+        }
+        return;
+    }
+
+    // =========================== compute waves ==============================================
+    const int team = wave >> 2;
+    const int wq = wave & 3;                                // pixel quarter of the 128 x 32 tile
+    const int frow = lane & 31, fk = lane >> 5;
+    const char* lds_b = reinterpret_cast<const char*>(lds);
+    const int arow = wq * 32 + frow;
+    const uint32_t a_base = (uint32_t)(arow * PITCH + (pw_swz<CPR>(arow, fk) << 4));
+    const uint32_t b_base = (uint32_t)(frow * PITCH + (pw_swz<CPR>(frow, fk) << 4));
+    char* stg = reinterpret_cast<char*>(lds) + A_BYTES + 4 * B_BYTES + wave * kPwStage;
+    const int c8 = lane & 7;
+
+    // y is addressed from the workgroup's first pixel; 128 rows of K outputs stay below 2^31 bytes (host)
+    const size_t y_off = (size_t)m0 * s.K;
+    const size_t y_rem = ((size_t)s.M * s.K - y_off) * sizeof(TO);
+    const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + y_off, 0, y_rem > kPwDrop ? kPwDrop : (uint32_t)y_rem, kRsrcFlags);
+
+    floatx16 acc;
+    // chunk 2*kk + fk of a row sits at (fk ^ swizzle) ^ 2*kk: the lane's address xor (kk << 5).
+    // The wave's pixel fragments, all K slices, stay in registers from here on.
+    frag_t areg[KK];
+    auto read_pixels = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) areg[kk] = *reinterpret_cast<const frag_t*>(lds_b + (a_base ^ (uint32_t)(kk << 5)));
+    };
+    // Filter fragments are read two K slices ahead.
+    auto multiply = [&](int slot) {
+        const char* pb = lds_b + pw_slot<CPR>(slot);
+        constexpr int AHEAD = 2;
+        frag_t b[AHEAD];
+#pragma unroll
+        for (int kk = 0; kk < AHEAD; ++kk) b[kk] = *reinterpret_cast<const frag_t*>(pb + (b_base ^ (uint32_t)(kk << 5)));
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk == 0) {
+                floatx16 z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                acc = Elem<T>::mfma32(b[kk % AHEAD], areg[kk], z);
+            } else {
+                acc = Elem<T>::mfma32(b[kk % AHEAD], areg[kk], acc);
+            }
+            if (kk + AHEAD < KK)
+                b[kk % AHEAD] = *reinterpret_cast<const frag_t*>(pb + (b_base ^ (uint32_t)((kk + AHEAD) << 5)));
+        }
+    };
+    // The filters are the MFMA's row operand: lane l holds pixel l%32 of the fragment and, in accumulator
+    // element v, filter 8*(v/4) + 4*(l/32) + v%4 of the tile's 32, which is what store_frag_staged expects.
+    auto write_out = [&](int tile) {
+        const int k_first = tile * kPwBN;
+        const bool pieces_ok = k_first + 4 * c8 + 3 < s.K;
+        const int r_first = wq * 32;
+        store_frag_staged<TO>(stg, acc, lane, y_rsrc, pieces_ok, [&](int i) -> uint32_t {
+            const int row = r_first + i;
+            return row < rows ? (uint32_t)(row * s.K + k_first) * (uint32_t)sizeof(TO) : kPwDrop;
+        });
+    };
+
+    wait_vmcnt<0>();
+    __syncthreads();
+    read_pixels();
+    for (int j = 0; j < NP; ++j) {
+        const int tile = 2 * j + team;
+        if (tile < NT) {
+            multiply(tile & (kPwSlots - 1));
+            write_out(tile);
+        }
+        __syncthreads();
+    }
+}
+
+bool plan_pw(const ConvShape& s, PwGeom* g) {
+    if (s.R != 1 || s.S != 1) return false;
+    if (s.C != 64 && s.C != 128 && s.C != 256) return false;
+    if ((s.K & 3) || s.P >= (1 << 14) || s.Q >= (1 << 14)) return false;
+    if ((long)s.K * s.C * 2 >= (1L << 31)) return false;
+    // pixels of one workgroup span at most 128 / PQ + 2 images; their bytes are addressed with 31 bits
+    const long img_bytes = (long)s.H * s.W * s.C * 2;
+    if ((kPwBM / s.PQ + 2) * img_bytes >= (1L << 31)) return false;
+    if ((long)kPwBM * s.K * 4 >= (1L << 31)) return false;
+    const long cus = device_cus();
+    const long rounds = (s.M + cus * kPwBM - 1) / (cus * kPwBM);
+    long nwg = cus * rounds;
+    if (nwg > s.M) nwg = s.M;
+    const long rows = (s.M + nwg - 1) / nwg;                 // <= 128
+    g->rows_per_wg = (int)rows;
+    g->tiles_n = (s.K + kPwBN - 1) / kPwBN;
+    g->inv_q = 1.0f / (float)s.Q;
+    g->inv_p = 1.0f / (float)s.P;
+    return true;
+}
+
+template <typename T, typename TO, int CPR>
+hipError_t launch_pw_t(const void* x, const void* w, void* y, const ConvShape& s, const PwGeom& g, hipStream_t st) {
+    constexpr int lds_bytes = (kPwBM + 4 * kPwBN) * CPR * 16 + 8 * kPwStage;
+    auto kern = ipw_kernel<T, TO, CPR>;
+    static std::atomic<bool> raised{false};
+    if (!raised.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        raised.store(true, std::memory_order_release);
+    }
+    const int nwg = (s.M + g.rows_per_wg - 1) / g.rows_per_wg;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kPwWaves * 64), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y, s, g);
+    return hipGetLastError();
+}
+
+template <typename T, typename TO>
+hipError_t launch_pw_c(const void* x, const void* w, void* y, const ConvShape& s, const PwGeom& g, hipStream_t st) {
+    switch (s.C) {
+        case 64: return launch_pw_t<T, TO, 8>(x, w, y, s, g, st);
+        case 128: return launch_pw_t<T, TO, 16>(x, w, y, s, g, st);
+        case 256: return launch_pw_t<T, TO, 32>(x, w, y, s, g, st);
+        default: return hipErrorInvalidConfiguration;
+    }
+}
+
+}  // namespace
+
+bool pointwise_supported(const ConvShape& s) {
+    PwGeom g;
+    return plan_pw(s, &g);
+}
+
+// Where it measured faster than the per-tap kernels: workgroups with (nearly) full pixel tiles -- the MFMAs always
+// run on 128 rows, and every workgroup streams all filters -- that either run as one round over the compute units
+// or are small enough (128 channels or fewer) for several to share a compute unit, so that one workgroup's start-up
+// hides behind another's stores.
+bool pointwise_preferred(const ConvShape& s) {
+    PwGeom g;
+    if (!plan_pw(s, &g) || g.rows_per_wg < 96) return false;
+    const long nwg = (s.M + g.rows_per_wg - 1) / g.rows_per_wg;
+    return nwg <= device_cus() || s.C <= 128;
+}
+
+hipError_t launch_pointwise(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t st) {
+    PwGeom g;
+    if (!plan_pw(s, &g)) return hipErrorInvalidConfiguration;
+    if (in_t == IN_BF16) {
+        if (out_t == OUT_F32) return launch_pw_c<bf16_t, float>(x, w, y, s, g, st);
+        if (out_t == OUT_BF16) return launch_pw_c<bf16_t, bf16_t>(x, w, y, s, g, st);
+    } else if (in_t == IN_F16) {
+        if (out_t == OUT_F32) return launch_pw_c<f16_t, float>(x, w, y, s, g, st);
+        if (out_t == OUT_F16) return launch_pw_c<f16_t, f16_t>(x, w, y, s, g, st);
+    }
+    return hipErrorInvalidConfiguration;
+}
+
+}  // namespace iconv

@@ -199,6 +199,35 @@ def test_resident_filter_kernels(B):
     assert ran >= 3 * 15
 
 
+def test_pixel_resident_kernel_for_1x1_layers(B):
+    """The 1x1 kernel that keeps a workgroup's pixels in LDS and streams the filter tiles through two teams of
+    compute waves (one multiplies while the other stores): 64, 128 and 256 channels, strides 1 to 3, padding (zero
+    rows), filter counts that leave the last tile of 64 ragged or are a single partial tile, one and many tiles (odd
+    and even counts: the team that finishes differs), several images per workgroup, one output row per workgroup,
+    workgroups of exactly 128 and of fewer pixels in two rounds, fp16, and 16-bit outputs."""
+    shapes = [workloads.small_layer("a_a", 2, 14, 14, 64, 64, 1, 1, 1, 0, 1, seed_id=860),      # one tile
+              workloads.small_layer("a_b", 3, 13, 9, 128, 200, 1, 1, 2, 0, 1, seed_id=861),     # stride 2, 4 tiles, last of 8 filters
+              workloads.small_layer("a_c", 2, 56, 56, 256, 512, 1, 1, 2, 0, 1, seed_id=862),    # the benchmark's 1x1 layer, two images
+              workloads.small_layer("a_d", 4, 7, 7, 256, 68, 1, 1, 1, 1, 1, seed_id=863),       # padding: 9x9 outputs with a zero border
+              workloads.small_layer("a_e", 5, 3, 3, 64, 4, 1, 1, 1, 0, 1, seed_id=864),         # 45 pixels, four filters
+              workloads.small_layer("a_f", 8, 64, 64, 64, 192, 1, 1, 1, 0, 1, dtype="f16", seed_id=865),   # 128 pixels per workgroup, 3 tiles
+              workloads.small_layer("a_g", 9, 64, 64, 128, 96, 1, 1, 1, 0, 1, seed_id=866),     # two rounds of workgroups of 72 pixels
+              workloads.small_layer("a_h", 1, 40, 33, 128, 320, 1, 1, 3, 0, 1, dtype="f16", seed_id=867)]  # stride 3, five tiles
+    names = variant_names(B)
+    v = [i for i, nm in enumerate(names) if nm.startswith("a128")]
+    assert len(v) == 1
+    for L in shapes:
+        assert B.iconv_variant_accepts(v[0], *L.shape_args(), code_of(L)), L.name
+        print("pixel-resident", L.name, flush=True)
+        check(B, L, variant=v[0])
+    for L in (shapes[1], shapes[3], shapes[7]):
+        print("pixel-resident 16-bit out", L.name, flush=True)
+        check_sixteen_bit(B, L, variant=v[0])
+    not_for_it = workloads.small_layer("a_x", 1, 9, 9, 96, 64, 1, 1, 1, 0, 1, seed_id=868)       # 96 channels
+    assert not B.iconv_variant_accepts(v[0], *not_for_it.shape_args(), code_of(not_for_it))
+    check(B, not_for_it, variant=v[0])                                                         # falls back, still the convolution
+
+
 def test_merged_tap_workgroups_walking_several_blocks(B):
     """The merged-tap kernel for 4-channel layers keeps its weights in LDS and double-buffers the
     input patch over a range of output blocks: uncapped (few blocks per workgroup) and capped to
