@@ -4,18 +4,17 @@
 // themselves: the per-tap decomposition of the paper (section 3.2) with a single tap.  Its cost on
 // this chip is the write of y, so the kernel is built around keeping the stores going:
 //
-//  * a workgroup owns up to 128 consecutive output pixels; their C channels are loaded into LDS once
-//    (the "A" operand stays resident) and the filters stream through a ring of eight slots in tiles of 32
-//    (eight loader waves -- a wave gets out only one global -> LDS load per 130-200 ns -- three tiles ahead: a tile takes about a microsecond to
-//    arrive from L2 under load, several times what multiplying it takes);
-//  * two TEAMS of four compute waves take the filter tiles in turn.  Time is cut into ticks by one
-//    workgroup barrier per filter tile: in tick k team k%2 multiplies tile k (four waves, 32 pixels x
-//    32 filters each; a wave reads the fragments of its 32 pixels from LDS once and keeps them in
-//    registers for all tiles, so a K step is one filter-fragment read and one MFMA), the other team
-//    writes out tile k-1 from
-//    its accumulators, and the loader waves request tile k+3 into the slot tile k-1 has left.  So
-//    from the second tick on stores, MFMAs and loads overlap, which a one-tile-per-workgroup kernel
-//    cannot do.
+//  * a workgroup owns up to 128 consecutive output pixels; their C channels are loaded into LDS once,
+//    and every compute wave takes the fragments of its 32 pixels into registers for the whole kernel,
+//    so a K step is one filter-fragment read and one MFMA;
+//  * the filters stream through a ring of eight LDS slots in tiles of 32 (eight loader waves, global ->
+//    LDS DMA), requested up to three pairs of tiles ahead of their use;
+//  * two TEAMS of four compute waves each take one tile of a pair (four waves x 32 pixels x 32 filters),
+//    multiply it and write it out through the staged stores; one workgroup barrier per pair hands the
+//    slots back to the loader waves.  Eight waves with a tile each keep the matrix pipe and the store
+//    path busier than one large tile per workgroup, and the next pairs land meanwhile.
+//    (A form in which one team multiplies while the other stores, tile by tile, measured slower: the
+//    two do not overlap well on one compute unit.)
 //
 // LDS: [pixels: 128 rows x 2C bytes][filters: 4 slots x 32 rows x 2C bytes][staging: 2 KiB per compute
 // wave]; once the pixel fragments are in registers the pixel region serves as four more filter slots.
