@@ -79,7 +79,7 @@ int iconv_probe_mfma(void *out, size_t out_bytes, int iters, int random_operands
 int iconv_probe_lds(void *out, size_t out_bytes, int iters, int pattern, void *stream);
 
 /* The chunk position the MFMA kernels give 16-byte chunk `chunk` of tile row `row` in LDS rows of
- * `chunks_per_row` (4 or 8) chunks - the very function the kernels compile, evaluated on the host, so that
+ * `chunks_per_row` (4, 8, 16 or 32) chunks - the very function the kernels compile, evaluated on the host, so that
  * the layout can be checked against the bank model without a GPU.  Returns -1 for other arguments. */
 int iconv_lds_swizzle(int chunks_per_row, int row, int chunk);
 

@@ -295,7 +295,9 @@ int iconv_lds_stage_offset(int pixel, int piece) {
 }
 
 int iconv_lds_swizzle(int chunks_per_row, int row, int chunk) {
-    if ((chunks_per_row != 4 && chunks_per_row != 8) || row < 0 || chunk < 0 || chunk >= chunks_per_row) return -1;
+    if ((chunks_per_row != 4 && chunks_per_row != 8 && chunks_per_row != 16 && chunks_per_row != 32) || row < 0 || chunk < 0 ||
+        chunk >= chunks_per_row)
+        return -1;
     return lds_swizzle(chunks_per_row, row, chunk);
 }
 

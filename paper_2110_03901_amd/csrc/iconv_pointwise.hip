@@ -19,9 +19,8 @@
 // LDS: [pixels: 128 rows x 2C bytes][filters: 4 slots x 32 rows x 2C bytes][staging: 2 KiB per compute
 // wave]; once the pixel fragments are in registers the pixel region serves as four more filter slots.
 // Rows hold their 16-byte chunks XOR-swizzled so that the MFMA operand read (32 consecutive
-// rows, one chunk per half-wave) is free of bank conflicts: rows of 256 bytes and more xor the low four
-// chunk bits with row % 16, 128-byte rows use swz<8>.  The DMA fills write lane-linear and apply the
-// swizzle on the global side.
+// rows, one chunk per half-wave) is free of bank conflicts (swz<CPR>, the function of the other MFMA
+// kernels).  The DMA fills write lane-linear and apply the swizzle on the global side.
 #include <atomic>
 
 #include "iconv_common.h"
@@ -45,11 +44,6 @@ struct PwGeom {
     int tiles_n;         // filter tiles of 32
     float inv_q, inv_p;  // 1 / Q, 1 / P
 };
-
-// chunk position of 16-byte chunk c of LDS row `row` (rows of CPR chunks)
-template <int CPR> __host__ __device__ __forceinline__ constexpr int pw_swz(int row, int c) {
-    return CPR >= 16 ? (c ^ (row & 15)) : swz<8>(row, c);
-}
 
 // Byte offset in LDS of filter-tile slot s (0..7).  Slots 0-3 follow the pixel region; slots 4-7 ARE the pixel
 // region, which is free once every compute wave has taken its pixel fragments into registers.
@@ -98,7 +92,7 @@ ipw_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y,
     const int r_in = lane / CPR, pc = lane % CPR;           // row within an instruction, physical chunk
     // global byte offset of the lane's chunk of pixel row `row` (0..127) of the workgroup, or kPwDrop
     auto a_offset = [&](int row) -> uint32_t {
-        const int lc = pw_swz<CPR>(row, pc);                // the swizzle is an involution on the chunk number
+        const int lc = swz<CPR>(row, pc);                // the swizzle is an involution on the chunk number
         const int qq = q0 + row;
         const int dp = (int)(((float)qq + 0.5f) * g.inv_q);     // exact: qq < Q + 128, Q < 2^14 (host)
         const int q = qq - dp * s.Q;
@@ -111,7 +105,7 @@ ipw_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y,
     };
     // global byte offset of the lane's chunk of filter row `row` (0..63) of filter tile `tile`
     auto b_offset = [&](int tile, int row) -> uint32_t {
-        const int lc = pw_swz<CPR>(row, pc);
+        const int lc = swz<CPR>(row, pc);
         const int k = tile * kPwBN + row;
         return k < s.K ? (uint32_t)(k * s.C + lc * 8) * 2u : kPwDrop;
     };
@@ -179,8 +173,8 @@ ipw_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y,
     const int frow = lane & 31, fk = lane >> 5;
     const char* lds_b = reinterpret_cast<const char*>(lds);
     const int arow = wq * 32 + frow;
-    const uint32_t a_base = (uint32_t)(arow * PITCH + (pw_swz<CPR>(arow, fk) << 4));
-    const uint32_t b_base = (uint32_t)(frow * PITCH + (pw_swz<CPR>(frow, fk) << 4));
+    const uint32_t a_base = (uint32_t)(arow * PITCH + (swz<CPR>(arow, fk) << 4));
+    const uint32_t b_base = (uint32_t)(frow * PITCH + (swz<CPR>(frow, fk) << 4));
     char* stg = reinterpret_cast<char*>(lds) + A_BYTES + 4 * B_BYTES + wave * kPwStage;
     const int c8 = lane & 7;
 

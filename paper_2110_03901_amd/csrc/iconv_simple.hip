@@ -325,7 +325,12 @@ hipError_t launch_lds_probe(void* out, int iters, int pattern, hipStream_t st) {
 int lds_stage_offset(int pixel, int piece) { return (int)stage_off(pixel, piece); }
 
 int lds_swizzle(int chunks_per_row, int row, int chunk) {
-    return chunks_per_row == 4 ? swz<4>(row, chunk) : swz<8>(row, chunk);
+    switch (chunks_per_row) {
+        case 4: return swz<4>(row, chunk);
+        case 8: return swz<8>(row, chunk);
+        case 16: return swz<16>(row, chunk);
+        default: return swz<32>(row, chunk);
+    }
 }
 
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {

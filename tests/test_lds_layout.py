@@ -78,13 +78,16 @@ def test_model_tells_layouts_apart():
     assert all(len({(addr[l] >> 4) & 15 for l in q}) == 16 for q in quarter)
 
 
-@pytest.mark.parametrize("cpr", [4, 8])
+@pytest.mark.parametrize("cpr", [4, 8, 16, 32])
 def test_tile_row_swizzle_is_a_permutation_and_conflict_free(lib, cpr):
-    """swz<CPR>: chunks of a row stay in the row (so the lane-linear LDS-DMA fill can apply it on the global
-    side), and the operand read of every fragment (32 consecutive rows from a multiple of 32, chunk
-    2*kk + l/32 for K slice kk) is conflict-free."""
+    """swz<CPR> (rows of 64 and 128 bytes in the per-tap and patch kernels, 128 to 512 bytes in the pixel-resident
+    1x1 kernel and the 128-channel filter stages): chunks of a row stay in the row (so the lane-linear LDS-DMA fill
+    can apply it on the global side), applying it twice gives the chunk back (the loaders use it in that direction),
+    and the operand read of every fragment (32 consecutive rows from a multiple of 32, chunk 2*kk + l/32 for K slice
+    kk) is conflict-free."""
     for row in range(512):
         assert sorted(lib.iconv_lds_swizzle(cpr, row, c) for c in range(cpr)) == list(range(cpr))
+        assert all(lib.iconv_lds_swizzle(cpr, row, lib.iconv_lds_swizzle(cpr, row, c)) == c for c in range(cpr))
     for base in range(0, 512, 32):
         for kk in range(cpr // 2):
             addr = [((base + (l & 31)) * cpr + lib.iconv_lds_swizzle(cpr, base + (l & 31), 2 * kk + (l >> 5))) * 16
