@@ -303,6 +303,9 @@ def main():
         a = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
         b = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
         t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3)
+        # launch-to-launch period of graph nodes that do next to nothing (a 16-byte copy): the part of every
+        # ms_per_step above that lies between kernels
+        t_gap = time_steps(lambda: B.iconv_probe_copy(b, a, 16), 500, 20)
         # LDS instruction cost: cycles per instruction and compute unit at the nominal 2.4 GHz
         lds_iters = 2000
         lds_cost = {}
@@ -314,7 +317,9 @@ def main():
                              "mfma_bf16_tflops_random_operands": round(probe_random, 1),
                              "copy_gbs_read_plus_write": round(2 * nb / (t_c * 1e-3) / 1e9, 1),
                              "value_frac_of_achievable_mfma": round(tflops / probe_tflops, 4),
-                             "lds_cycles_per_b128_instruction_per_cu": lds_cost}
+                             "lds_cycles_per_b128_instruction_per_cu": lds_cost,
+                             "graph_node_period_us_empty_kernel": round(t_gap * 1e3, 3),
+                             "headline_kernel_us_without_that_period": round((ms - t_gap) * 1e3, 3)}
         del a, b, pout
         torch.cuda.empty_cache()
 

@@ -40,6 +40,11 @@ struct PatchGeom {
     // row v of the tile is row v % TH of image v / TH, patch row v is row v % PH of image v / PH.
     int G;               // images per tile (1 unless the whole map fits a tile at least twice)
     float inv_th, inv_ph;
+    // Tile order.  0: filter tile fastest (neighbouring workgroups share an input patch).  1: filter tile slowest, so
+    // that the workgroups of one XCD (a contiguous range of tile numbers) read few filter tiles and these stay in that
+    // XCD's L2 -- for layers whose filters outweigh their input (the 7 x 7 maps with 512 channels).
+    int n_slow;
+    int tiles_m;         // tiles per filter tile (total_tiles / tiles_n)
 };
 
 // Patch swizzle.  The patch is an array of 256-byte windows (all 64 LDS banks), each holding
@@ -91,7 +96,14 @@ struct TileCoord {
 
 template <int BN> __device__ __forceinline__ TileCoord decode_tile(int t, const PatchGeom& g) {
     TileCoord c;
-    const int tile_n = t % g.tiles_n; t /= g.tiles_n;
+    int tile_n;
+    if (g.n_slow) {
+        tile_n = t / g.tiles_m;
+        t -= tile_n * g.tiles_m;
+    } else {
+        tile_n = t % g.tiles_n;
+        t /= g.tiles_n;
+    }
     const int tile_w = t % g.tiles_w; t /= g.tiles_w;
     const int tile_h = t % g.tiles_h;
     c.n = (t / g.tiles_h) * g.G;
@@ -745,6 +757,9 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
     const int occ = cached_occupancy(occ_slot, (const void*)kern, c.waves() * 64, lds_bytes);
     int nwg = 1;
     g.total_tiles = (int)total;
+    g.tiles_m = (int)(total / g.tiles_n);
+    const long w_bytes = (long)s.K * s.Kg * 2, x_bytes = (long)s.N * s.H * s.W * s.C * 2;
+    g.n_slow = (g.tiles_n > 1 && w_bytes >= (2L << 20) && w_bytes > x_bytes) ? 1 : 0;
     const int cap = call_max_workgroups();
     if (cap > 0) {
         split_tiles(total, cap, 1, &g.tiles_per_wg, &nwg);
