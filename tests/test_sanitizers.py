@@ -110,7 +110,9 @@ assert lib.iconv_fwd_explicit_noalloc(a, a, a, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1
 assert lib.iconv_workspace_bytes(1, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1, 1) == 100352 * 576 * 2
 assert lib.iconv_workspace_bytes(1, 1, 2, 2, 1, 1, 3, 3, 1, 0, 1, 1) == 0
 for args in [(32, 56, 56, 64, 64, 3, 3, 1, 1, 1, 1), (64, 7, 7, 512, 512, 3, 3, 1, 1, 1, 1), (64, 224, 224, 4, 64, 7, 7, 2, 3, 1, 1),
-             (3, 17, 19, 8, 8, 1, 1, 1, 0, 1, 2), (2147483647, 1, 1, 8, 8, 1, 1, 1, 0, 1, 1), (1, 1, 1, 8, 1, 1, 1, 1, 2147483647, 1, 1)]:
+             (3, 17, 19, 8, 8, 1, 1, 1, 0, 1, 2), (2147483647, 1, 1, 8, 8, 1, 1, 1, 0, 1, 1), (1, 1, 1, 8, 1, 1, 1, 1, 2147483647, 1, 1),
+             (32, 56, 56, 256, 512, 1, 1, 2, 0, 1, 1), (2147483647, 1, 1, 64, 8, 1, 1, 1, 0, 1, 1), (1, 16383, 16383, 64, 4, 1, 1, 1, 0, 1, 1),
+             (4, 16384, 8, 128, 2147483644, 1, 1, 1, 0, 1, 1)]:
     lib.iconv_kernel_for(*args)
 for v in range(-2, lib.iconv_num_variants() + 2):
     lib.iconv_variant_accepts(v, 2, 24, 24, 64, 64, 3, 3, 1, 1, 1, 1)
