@@ -78,9 +78,14 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
 
-    def time_steps(fn, steps, warmup, repeats=1):
+    def time_steps(fn, steps, warmup, repeats=1, keep_busy=False):
         """ms per step over exactly `steps` steps after `warmup` untimed ones; with repeats > 1 the graph of
-        `steps` launches is replayed that many times and the median replay is reported."""
+        `steps` launches is replayed that many times and the median replay is reported.  keep_busy (the short
+        graphs of the per-layer, explicit and study tables): each timed replay directly follows untimed replays of
+        the same graph worth about 5 ms, with no synchronisation in between -- after an idle moment the chip runs
+        its first few milliseconds at lower clocks (cfg2: 15.5 us per launch in a graph of 20, 14.1 in one of 200,
+        13.2 from 1000 on), which a short graph would otherwise be charged with.  The headline does not use it:
+        its `steps` launches are bracketed by synchronisations on both sides, as the contract asks."""
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
@@ -101,7 +106,16 @@ def main():
                     fn()
         torch.cuda.synchronize()
         times = []
+        n_busy = 0
+        if keep_busy:
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            n_busy = max(1, min(200, int(5.0 / max(e0.elapsed_time(e1), 1e-3)) + 1))
         for _ in range(max(1, repeats)):
+            for _ in range(n_busy):
+                graph.replay()
             e0.record()
             graph.replay()
             e1.record()
@@ -178,7 +192,7 @@ def main():
             turn[0] += 1
             B.iconv_fwd(xs, wd0, ys, *sa0, code)
         n_cold = max(n_sets * 4, min(args.steps, 400))
-        ms_cold = time_steps(cold_step, n_cold, n_sets)
+        ms_cold = time_steps(cold_step, n_cold, n_sets, keep_busy=True)
         out["cold"] = {"ms_per_step": round(ms_cold, 6), "tflops": round(L.flops / (ms_cold * 1e-3) / 1e12, 2),
                        "gbs_algorithmic": round(L.algorithmic_bytes(4) / (ms_cold * 1e-3) / 1e9, 1),
                        "buffer_sets": n_sets, "bytes_between_reuse": n_sets * pair_bytes, "steps": n_cold}
@@ -190,9 +204,9 @@ def main():
         sa = Li.shape_args()
         ws_bytes = B.iconv_workspace_bytes(B.ALGO_EXPLICIT, *sa, code_i)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
-        ms_full = time_steps(lambda: B.iconv_fwd_explicit(xd, wd, y, ws, ws_bytes, *sa, code_i), n_exp, 5, repeats=3)
+        ms_full = time_steps(lambda: B.iconv_fwd_explicit(xd, wd, y, ws, ws_bytes, *sa, code_i), n_exp, 5, repeats=3, keep_busy=True)
         ms_low = time_steps(lambda: B.iconv_im2col(xd, ws, ws_bytes, Li.N, Li.H, Li.W, Li.C, Li.R, Li.S, Li.stride, Li.pad,
-                                                   Li.dilation, code_i), n_exp, 5, repeats=3)
+                                                   Li.dilation, code_i), n_exp, 5, repeats=3, keep_busy=True)
         del ws
         torch.cuda.empty_cache()
         x_bytes = Li.N * Li.H * Li.W * Li.C * Li.elt_bytes()
@@ -213,7 +227,7 @@ def main():
         for name, Li in workloads.LAYERS.items():
             _, _, ri, keep = prepare(Li)
             n = max(50, args.steps // 10)
-            mi = time_steps(ri, n, max(20, args.warmup // 4), repeats=5)       # median of five replays of n launches
+            mi = time_steps(ri, n, max(20, args.warmup // 4), repeats=5, keep_busy=True)   # median of five replays of n launches
             bi, tf, gb = bound_of(Li, mi)
             tf_real = Li.flops_real / (mi * 1e-3) / 1e12
             layers[name] = {"us": round(mi * 1e3, 3), "tflops": round(tf_real, 2), "bound": bi,
@@ -240,7 +254,7 @@ def main():
             xd, wd = B.to_device(x, c), B.to_device(w, c)
             y = B.empty_output(Li.N, Li.P, Li.Q, Li.K, c)
             sa = Li.shape_args()
-            t = time_steps(lambda: B.iconv_fwd(xd, wd, y, *sa, c), 100, 20, repeats=5)
+            t = time_steps(lambda: B.iconv_fwd(xd, wd, y, *sa, c), 100, 20, repeats=5, keep_busy=True)
             del xd, wd, y
             torch.cuda.empty_cache()
             return t
@@ -252,7 +266,7 @@ def main():
             wd = B.to_device(w, c).permute(0, 3, 1, 2).contiguous()
             y = B.empty_output(Li.N, Li.P, Li.Q, Li.K, c)
             sa = Li.shape_args()
-            t = time_steps(lambda: B.iconv_fwd_channel_last(xd, wd, y, *sa, c), 50, 10)
+            t = time_steps(lambda: B.iconv_fwd_channel_last(xd, wd, y, *sa, c), 50, 10, keep_busy=True)
             del xd, wd, y
             torch.cuda.empty_cache()
             return t
@@ -295,22 +309,22 @@ def main():
         iters = 2000
         pout = torch.empty(B.MFMA_PROBE_GROUPS * 256, dtype=torch.float32, device="cuda:0")
         probe_flop = B.MFMA_PROBE_GROUPS * 4 * iters * 8 * 32768
-        t_m = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters), 20, 3)
+        t_m = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters), 20, 3, keep_busy=True)
         probe_tflops = probe_flop / (t_m * 1e-3) / 1e12
-        t_r = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters, True), 20, 3)
+        t_r = time_steps(lambda: B.iconv_probe_mfma(pout, pout.numel() * 4, iters, True), 20, 3, keep_busy=True)
         probe_random = probe_flop / (t_r * 1e-3) / 1e12
         nb = 256 << 20
         a = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
         b = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
-        t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3)
+        t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3, keep_busy=True)
         # launch-to-launch period of graph nodes that do next to nothing (a 16-byte copy): the part of every
         # ms_per_step above that lies between kernels
-        t_gap = time_steps(lambda: B.iconv_probe_copy(b, a, 16), 500, 20)
+        t_gap = time_steps(lambda: B.iconv_probe_copy(b, a, 16), 500, 20, keep_busy=True)
         # LDS instruction cost: cycles per instruction and compute unit at the nominal 2.4 GHz
         lds_iters = 2000
         lds_cost = {}
         for pi, pname in enumerate(B.LDS_PROBE_PATTERNS):
-            t_l = time_steps(lambda: B.iconv_probe_lds(pout, pout.numel() * 4, lds_iters, pi), 10, 2)
+            t_l = time_steps(lambda: B.iconv_probe_lds(pout, pout.numel() * 4, lds_iters, pi), 10, 2, keep_busy=True)
             lds_cost[pname] = round(t_l * 1e-3 * 2.4e9 / (B.MFMA_PROBE_GROUPS / 256 * 4 * lds_iters * 8), 2)
         out["achievable"] = {"mfma_bf16_tflops": round(probe_tflops, 1),
                              "mfma_frac_of_datasheet": round(probe_tflops / PEAK_MFMA_TFLOPS, 4),
