@@ -550,6 +550,8 @@ LARGE = [
     ("large_s1", 20, 1024, 1024, 64, 8, 3, 3, 1, 1, 1),
     ("large_s2", 20, 1024, 1024, 64, 16, 3, 3, 2, 1, 1),
     ("large_stem", 20, 4096, 4096, 4, 16, 7, 7, 2, 3, 1),
+    ("large_1x1", 20, 1024, 1024, 64, 72, 1, 1, 1, 0, 1),          # pixel-resident kernel, 163840 workgroups, y of 6 GB
+    ("large_1x1_s2", 20, 1024, 1024, 64, 136, 1, 1, 2, 0, 1),      # the same with sampled rows, y of 2.9 GB
 ]
 
 
