@@ -612,14 +612,16 @@ def test_side_streams_give_the_same_bits(B):
 
 def test_graph_replays_match_eager_runs(B):
     """The timed configuration is a HIP-graph replay: one graph holding a launch of each kernel family
-    (resident-filter, patch-reuse with staged output, per-tap, merged-tap stem, fp32 direct) is
+    (resident-filter, patch-reuse with staged output, per-tap, merged-tap stem, fp32 direct, pixel-resident 1x1) is
     replayed four times, with new inputs written eagerly into the same buffers and a device
     synchronisation between replays; every replay must give the bits of the eager call on those inputs."""
     layers = [(workloads.small_layer("gr_res", 4, 28, 28, 64, 64, 3, 3, 1, 1, 1, seed_id=870), 1),
               (workloads.small_layer("gr_patch", 2, 24, 24, 64, 128, 3, 3, 1, 2, 2, seed_id=871), 1),
               (workloads.small_layer("gr_tap", 2, 30, 30, 128, 160, 3, 3, 2, 1, 1, seed_id=872), 3),
               (workloads.small_layer("gr_stem", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1, seed_id=873), 1),
-              (workloads.small_layer("gr_f32", 1, 9, 9, 5, 7, 3, 3, 1, 1, 1, dtype="f32", seed_id=874), 0)]
+              (workloads.small_layer("gr_f32", 1, 9, 9, 5, 7, 3, 3, 1, 1, 1, dtype="f32", seed_id=874), 0),
+              (workloads.small_layer("gr_1x1", 8, 56, 56, 128, 96, 1, 1, 1, 0, 1, seed_id=875), 1)]
+    assert B.iconv_kernel_for(*layers[-1][0].shape_args(), 1).startswith("a128")     # the pixel-resident 1x1 kernel
     bufs = []
     for L, code in layers:
         x, w = workloads.make_inputs(L)
