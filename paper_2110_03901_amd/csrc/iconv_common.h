@@ -82,7 +82,8 @@ int resident_choose(const ConvShape& s);   // best variant or -1
 hipError_t launch_resident(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
                            hipStream_t stream);
 
-// Resident-filter kernels phased by filter row, one LDS row per pixel (C == 32 or 64); variants 0, 1 = 7, 8 fragments.
+// Resident-filter kernels phased by filter row, one LDS row per pixel (C == 32 or 64); variants 0, 1 = 7, 8 fragments
+// with four compute and four loader waves, 2, 3 = the same with all eight waves computing (one block per workgroup).
 bool rowres_supported(const ConvShape& s, int v);
 bool rowres_plan_cost(const ConvShape& s, int v, double* cost, long* blocks);
 hipError_t launch_rowres(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t stream);

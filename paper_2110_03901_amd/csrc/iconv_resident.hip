@@ -450,8 +450,8 @@ hipError_t launch_res_mf(const void* x, const void* w, void* y, const ConvShape&
 
 constexpr int kResMF[] = {7, 8};
 // r: channel-slice phases (this file); t: filter-row phases, whole pixels per LDS row (iconv_rowres.hip)
-const char* const kResNames[] = {"r448x64_f7_4+4", "r512x64_f8_4+4", "t448x64_f7_4+4", "t512x64_f8_4+4"};
-constexpr int kNumRes = 4;
+const char* const kResNames[] = {"r448x64_f7_4+4", "r512x64_f8_4+4", "t448x64_f7_4+4", "t512x64_f8_4+4", "s448x64_f7_8", "s512x64_f8_8"};
+constexpr int kNumRes = 6;
 
 }  // namespace
 
@@ -490,7 +490,11 @@ int resident_choose(const ConvShape& s) {
             blocks = ok ? g.total_tiles : 0;
         }
         if (!ok || blocks < enough) continue;
-        if (best < 0 || c < best_cost || (v >= 2 && best < 2 && c <= best_cost)) {
+        // the all-compute form ("s") has one block per workgroup: it is for launches of one round of workgroups,
+        // where it measured 6-16 % faster; with more blocks the persistent forms load the next block under the stores
+        if (v >= 4 && blocks > cus) continue;
+        // on equal cost: filter-row phases ("t") before channel-slice phases ("r"), all-compute ("s") before both
+        if (best < 0 || c < best_cost || (c <= best_cost && ((v >= 2 && best < 2) || (v >= 4 && best < 4)))) {
             best = v;
             best_cost = c;
         }

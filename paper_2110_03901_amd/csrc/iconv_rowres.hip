@@ -95,7 +95,7 @@ __device__ __forceinline__ void wait_vmcnt_upto(int n) {
     }
 }
 
-template <typename T, typename TO, int MF, int S_, int CPR>
+template <typename T, typename TO, int MF, int S_, int CPR, int SPLIT>
 __global__ void __launch_bounds__((kRowWaves + kRowLoaders) * 64)
 irow_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const RowGeom g) {
     typedef typename Elem<T>::frag frag_t;
@@ -194,7 +194,7 @@ irow_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     const uint32_t col_ok0 = column_mask(tc0);
     pending[0] = issue_phase(tc0, col_ok0, 0, wave, NWAVES, true);
 
-    if (wave >= kRowWaves) {
+    if (SPLIT == 0 && wave >= kRowWaves) {
         // =========================== loader waves ===========================================
         __builtin_amdgcn_s_setprio(3);
         const int lw = wave - kRowWaves;
@@ -233,144 +233,175 @@ irow_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     }
 
     // =============================== compute waves ==============================================
-    const int frow = lane & 31, fk = lane >> 5;
-    const int m_half = wave >> 1, nh = wave & 1;
-    const int npx = g.TH * g.TW;
-    const char* lds_b = reinterpret_cast<const char*>(lds);
-    // Byte offset in the patch of the lane's operand of fragment mf, tap column s, filter row 0 and
-    // K step 0: pixel (th*stride, tw*stride + s*dil), chunk l/32.  K step kk: chunk 2*kk + l/32, i.e. the
-    // offset xor (kk << 5); a filter row further down adds a multiple of 16 rows, which leaves the
-    // swizzle term alone apart from the skew bit.  So: one (a ^ mask) + row offset per operand read.
-    uint32_t a_addr[MF][S_];
+    // SPLIT == 0: waves 0-3 compute all MF fragments of their (pixel half, filter half).  SPLIT == 1 (one block per
+    // workgroup): the four waves that issue the later phases compute as well -- waves 0-3 take fragments 0 .. MFA-1,
+    // waves 4-7 issue phase r + 1 after barrier r and then take fragments MFA .. MF-1 -- so that every SIMD has two
+    // waves with MFMAs to issue and one hides the other's operand reads and address arithmetic.
+    constexpr int MFA = SPLIT ? (MF + 1) / 2 : MF;
+    auto compute = [&](auto f0_t, auto nf_t, auto issues_t) {
+        constexpr int F0 = decltype(f0_t)::value, NF = decltype(nf_t)::value;
+        constexpr bool ISSUES = decltype(issues_t)::value;
+        const int frow = lane & 31, fk = lane >> 5;
+        const int wv = wave & 3;
+        const int m_half = wv >> 1, nh = wv & 1;
+        const int npx = g.TH * g.TW;
+        const char* lds_b = reinterpret_cast<const char*>(lds);
+        // Byte offset in the patch of the lane's operand of fragment mf, tap column s, filter row 0 and
+        // K step 0: pixel (th*stride, tw*stride + s*dil), chunk l/32.  K step kk: chunk 2*kk + l/32, i.e. the
+        // offset xor (kk << 5); a filter row further down adds a multiple of 16 rows, which leaves the
+        // swizzle term alone apart from the skew bit.  So: one (a ^ mask) + row offset per operand read.
+        uint32_t a_addr[NF][S_];
 #pragma unroll
-    for (int mf = 0; mf < MF; ++mf) {
-        const int t = (m_half * MF + mf) * 32 + frow;
-        const int th = (int)(((float)t + 0.5f) * g.inv_tw);
-        const int tw = t - th * g.TW;
+        for (int mf = 0; mf < NF; ++mf) {
+            const int t = (m_half * MF + F0 + mf) * 32 + frow;
+            const int th = (int)(((float)t + 0.5f) * g.inv_tw);
+            const int tw = t - th * g.TW;
 #pragma unroll
-        for (int sc = 0; sc < S_; ++sc) {
-            const int pix = t < npx ? (th * g.PWp + tw) * s.stride + sc * s.dil : sc * s.dil;
-            const int odd_row = t < npx ? (g.skew & th & 1) << (SWB - 1) : 0;       // skew implies stride 1: patch row = th
-            a_addr[mf][sc] = (uint32_t)(pix * RB + ((fk ^ ((pix >> SWS) & (CPR - 1)) ^ odd_row) << 4));
+            for (int sc = 0; sc < S_; ++sc) {
+                const int pix = t < npx ? (th * g.PWp + tw) * s.stride + sc * s.dil : sc * s.dil;
+                const int odd_row = t < npx ? (g.skew & th & 1) << (SWB - 1) : 0;       // skew implies stride 1: patch row = th
+                a_addr[mf][sc] = (uint32_t)(pix * RB + ((fk ^ ((pix >> SWS) & (CPR - 1)) ^ odd_row) << 4));
+            }
         }
-    }
-    const uint32_t row_step = (uint32_t)(s.dil * g.PWp * RB);
-    // filter fragment of (tap, K step kk): filter f = 32*nh + l%32, chunk 2*kk + l/32
-    const int f_lane = nh * 32 + frow;
-    const uint32_t b_lane = (uint32_t)(f_lane * RB + ((fk ^ ((f_lane >> SWS) & (CPR - 1))) << 4));
-    // output staging, 16 pixels x 32 filters at a time: piece c (16 bytes, 4 filters) of pixel i at
-    // stage_off(i, c)
-    char* stg = reinterpret_cast<char*>(lds) + g.w_bytes + g.patch_bytes + wave * kRowStage;
-    const int f16 = frow & 15;
-    const uint32_t sw0 = stage_off(f16, fk);        // piece 2*gq + fk: xor (gq << 5)
-    const int l8 = lane >> 3, c8 = lane & 7;
-    const uint32_t sr0 = stage_off(l8, c8);          // pixel l/8 (+8), piece l%8
-    const uint32_t sr1 = stage_off(l8 + 8, c8);
-    const size_t y_elems = (size_t)s.M * s.K;
-    const bool k_ok = nh * 32 + 4 * c8 + 3 < s.K;
+        const uint32_t row_step = (uint32_t)(s.dil * g.PWp * RB);
+        // filter fragment of (tap, K step kk): filter f = 32*nh + l%32, chunk 2*kk + l/32
+        const int f_lane = nh * 32 + frow;
+        const uint32_t b_lane = (uint32_t)(f_lane * RB + ((fk ^ ((f_lane >> SWS) & (CPR - 1))) << 4));
+        // output staging, 16 pixels x 32 filters at a time: piece c (16 bytes, 4 filters) of pixel i at
+        // stage_off(i, c).  The waves that also load have no staging area of their own: they use the LDS rows of
+        // filter row 0, which no wave reads after the barrier that opens filter row 1 (the host asks for R >= 2).
+        char* stg = reinterpret_cast<char*>(lds) + (ISSUES ? wv * kRowStage : g.w_bytes + g.patch_bytes + wave * kRowStage);
+        const int f16 = frow & 15;
+        const uint32_t sw0 = stage_off(f16, fk);        // piece 2*gq + fk: xor (gq << 5)
+        const int l8 = lane >> 3, c8 = lane & 7;
+        const uint32_t sr0 = stage_off(l8, c8);          // pixel l/8 (+8), piece l%8
+        const uint32_t sr1 = stage_off(l8 + 8, c8);
+        const size_t y_elems = (size_t)s.M * s.K;
+        const bool k_ok = nh * 32 + 4 * c8 + 3 < s.K;
 
-    floatx16 acc[MF];
+        floatx16 acc[NF];
 
-    // ---- the K loop of filter row r: K steps (s, kk) = (0,0) .. (0,KK-1), (1,0), ...  In every step
-    // the filter fragment of the next step is read into the other B register set first, and each pixel
-    // fragment is re-read for the next step as soon as its MFMA has been issued, so the LDS reads of a
-    // step run under the MFMAs of the step before.  The last step of a row reads ahead into the row
-    // `r_ahead` (the next row if its data is known to have landed, else this row again: harmless).
-    auto fetch_a = [&](int mf, int sc, uint32_t mask, uint32_t roff_v) {
-        uint32_t addr;
-        asm volatile("v_xad_u32 %0, %1, %2, %3" : "=v"(addr) : "v"(a_addr[mf][sc]), "s"(mask), "v"(roff_v));
-        return *reinterpret_cast<const frag_t __attribute__((address_space(3)))*>(addr);
-    };
-    auto fetch_b = [&](int tap, int kk) {
-        return *reinterpret_cast<const frag_t*>(lds_b + tap * (kRowBN * RB) + (b_lane ^ (uint32_t)(kk << 5)));
-    };
-    auto flipped = [&](int r) { return (uint32_t)(g.skew & (r * s.dil) & 1) * kSkewBit; };
-    frag_t af[MF], b0, b1;
-    auto row = [&](int r, auto first) {
-        uint32_t roff = patch_base + (uint32_t)r * row_step;
-        asm volatile("" : "+v"(roff));          // one copy in a vector register for the whole row
-        const uint32_t mask_c = flipped(r);
-        // the row's first operands
-        b0 = fetch_b(r * S_, 0);
+        // ---- the K loop of filter row r: K steps (s, kk) = (0,0) .. (0,KK-1), (1,0), ...  In every step
+        // the filter fragment of the next step is read into the other B register set first, and each pixel
+        // fragment is re-read for the next step as soon as its MFMA has been issued, so the LDS reads of a
+        // step run under the MFMAs of the step before.
+        auto fetch_a = [&](int mf, int sc, uint32_t mask, uint32_t roff_v) {
+            uint32_t addr;
+            asm volatile("v_xad_u32 %0, %1, %2, %3" : "=v"(addr) : "v"(a_addr[mf][sc]), "s"(mask), "v"(roff_v));
+            return *reinterpret_cast<const frag_t __attribute__((address_space(3)))*>(addr);
+        };
+        auto fetch_b = [&](int tap, int kk) {
+            return *reinterpret_cast<const frag_t*>(lds_b + tap * (kRowBN * RB) + (b_lane ^ (uint32_t)(kk << 5)));
+        };
+        auto flipped = [&](int r) { return (uint32_t)(g.skew & (r * s.dil) & 1) * kSkewBit; };
+        frag_t af[NF], b0, b1;
+        auto row = [&](int r, auto first) {
+            uint32_t roff = patch_base + (uint32_t)r * row_step;
+            asm volatile("" : "+v"(roff));          // one copy in a vector register for the whole row
+            const uint32_t mask_c = flipped(r);
+            // the row's first operands
+            b0 = fetch_b(r * S_, 0);
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf) af[mf] = fetch_a(mf, 0, mask_c, roff);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int st = 0; st < KK * S_; ++st) {
-            const bool last = st + 1 == KK * S_;
-            const int sc_n = last ? 0 : (st + 1) / KK, kk_n = last ? 0 : (st + 1) % KK;
-            frag_t& bc = (st & 1) ? b1 : b0;
-            frag_t& bn = (st & 1) ? b0 : b1;
-            if (!last) bn = fetch_b(r * S_ + sc_n, kk_n);
+            for (int mf = 0; mf < NF; ++mf) af[mf] = fetch_a(mf, 0, mask_c, roff);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                if (decltype(first)::value && st == 0) {
-                    floatx16 z;
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) z[v] = 0.f;
-                    acc[mf] = Elem<T>::mfma32(bc, af[mf], z);
-                } else {
-                    acc[mf] = Elem<T>::mfma32(bc, af[mf], acc[mf]);
-                }
-                if (!last) af[mf] = fetch_a(mf, sc_n, mask_c ^ (uint32_t)(kk_n << 5), roff);
+            for (int st = 0; st < KK * S_; ++st) {
+                const bool last = st + 1 == KK * S_;
+                const int sc_n = last ? 0 : (st + 1) / KK, kk_n = last ? 0 : (st + 1) % KK;
+                frag_t& bc = (st & 1) ? b1 : b0;
+                frag_t& bn = (st & 1) ? b0 : b1;
+                if (!last) bn = fetch_b(r * S_ + sc_n, kk_n);
                 __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    };
-
-    // ---- the epilogue of a block.  The filters are the MFMA's row operand: lane l holds pixel l%32 of
-    // fragment mf and, in accumulator element v, filter 32*nh + 8*(v/4) + 4*(l/32) + v%4.  Half a
-    // fragment (16 pixels x 32 filters) at a time goes through the wave's staging area (in-order LDS,
-    // no wait needed in between) and leaves as 16-byte pieces, 8 lanes per pixel = one 128-byte line.
-    auto epilogue = [&](const RowTile& tc) {
-        const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
-        const size_t rem = (y_elems - org) * sizeof(TO);
-        const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0xffffffffull ? 0xffffffffu : (uint32_t)rem,
-                                                               kRsrcFlags);
-        int l8v = l8;
-        asm volatile("" : "+v"(l8v));           // the pixel arithmetic below is redone per block, not kept across the K loop
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf) {
-            u32x4 out[2][2];
+                for (int mf = 0; mf < NF; ++mf) {
+                    if (decltype(first)::value && st == 0) {
+                        floatx16 z;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                __builtin_amdgcn_wave_barrier();
-                if ((frow >> 4) == h) {
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        floatx4 v = {acc[mf][4 * gq], acc[mf][4 * gq + 1], acc[mf][4 * gq + 2], acc[mf][4 * gq + 3]};
-                        *reinterpret_cast<floatx4*>(stg + (sw0 ^ (uint32_t)(gq << 5))) = v;
+                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                        acc[mf] = Elem<T>::mfma32(bc, af[mf], z);
+                    } else {
+                        acc[mf] = Elem<T>::mfma32(bc, af[mf], acc[mf]);
                     }
+                    if (!last) af[mf] = fetch_a(mf, sc_n, mask_c ^ (uint32_t)(kk_n << 5), roff);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_wave_barrier();
-                out[h][0] = *reinterpret_cast<const u32x4*>(stg + sr0);
-                out[h][1] = *reinterpret_cast<const u32x4*>(stg + sr1);
             }
+        };
+
+        // ---- the epilogue of a block.  The filters are the MFMA's row operand: lane l holds pixel l%32 of
+        // fragment mf and, in accumulator element v, filter 32*nh + 8*(v/4) + 4*(l/32) + v%4.  Half a
+        // fragment (16 pixels x 32 filters) at a time goes through the wave's staging area (in-order LDS,
+        // no wait needed in between) and leaves as 16-byte pieces, 8 lanes per pixel = one 128-byte line.
+        auto epilogue = [&](const RowTile& tc) {
+            const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
+            const size_t rem = (y_elems - org) * sizeof(TO);
+            const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0xffffffffull ? 0xffffffffu : (uint32_t)rem,
+                                                                   kRsrcFlags);
+            int l8v = l8;
+            asm volatile("" : "+v"(l8v));           // the pixel arithmetic below is redone per block, not kept across the K loop
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int mf = 0; mf < NF; ++mf) {
+                u32x4 out[2][2];
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int t = (m_half * MF + mf) * 32 + h * 16 + 8 * j + l8v;
-                    const int th = (int)(((float)t + 0.5f) * g.inv_tw);
-                    const int tw = t - th * g.TW;
-                    const bool ok = k_ok & (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q);
-                    const uint32_t off = (uint32_t)((th * s.Q + tw) * s.K + nh * 32 + 4 * c8) * (uint32_t)sizeof(TO);
-                    if (ok) store_piece<TO>(out[h][j], y_rsrc, off);
+                for (int h = 0; h < 2; ++h) {
+                    __builtin_amdgcn_wave_barrier();
+                    if ((frow >> 4) == h) {
+#pragma unroll
+                        for (int gq = 0; gq < 4; ++gq) {
+                            floatx4 v = {acc[mf][4 * gq], acc[mf][4 * gq + 1], acc[mf][4 * gq + 2], acc[mf][4 * gq + 3]};
+                            *reinterpret_cast<floatx4*>(stg + (sw0 ^ (uint32_t)(gq << 5))) = v;
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    out[h][0] = *reinterpret_cast<const u32x4*>(stg + sr0);
+                    out[h][1] = *reinterpret_cast<const u32x4*>(stg + sr1);
                 }
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int t = (m_half * MF + F0 + mf) * 32 + h * 16 + 8 * j + l8v;
+                        const int th = (int)(((float)t + 0.5f) * g.inv_tw);
+                        const int tw = t - th * g.TW;
+                        const bool ok = k_ok & (t < npx) & (tc.p0 + th < s.P) & (tc.q0 + tw < s.Q);
+                        const uint32_t off = (uint32_t)((th * s.Q + tw) * s.K + nh * 32 + 4 * c8) * (uint32_t)sizeof(TO);
+                        if (ok) store_piece<TO>(out[h][j], y_rsrc, off);
+                    }
+            }
+        };
+
+        if constexpr (SPLIT == 0) {
+            wait_vmcnt<0>();                        // this wave's share of the first block's phase 0
+            for (int b = 0; b < nblocks; ++b) {
+                __syncthreads();                    // filter row 0 and its patch rows are in LDS
+                row(0, std::true_type{});
+                for (int r = 1; r < R; ++r) {
+                    __syncthreads();                // filter row r and the patch rows it adds are in LDS
+                    row(r, std::false_type{});
+                }
+                if (b + 1 < nblocks) __syncthreads();   // the patch may be overwritten
+                epilogue(b == 0 ? tc0 : row_decode(t_begin + b, g));
+            }
+        } else {
+            // one block: every wave waits for its own loads of the phase, the barrier makes the phase complete,
+            // and the waves that load issue the next phase before they start on the row
+            int in_flight = 0;
+            for (int r = 0; r < R; ++r) {
+                wait_vmcnt<0>();
+                __syncthreads();                    // filter row r and the patch rows it adds are in LDS
+                if (ISSUES && r + 1 < R) in_flight = issue_phase(tc0, col_ok0, r + 1, wv, kRowLoaders, true);
+                if (r == 0) row(0, std::true_type{});
+                else row(r, std::false_type{});
+            }
+            (void)in_flight;
+            epilogue(tc0);
         }
     };
-
-    wait_vmcnt<0>();                            // this wave's share of the first block's phase 0
-    for (int b = 0; b < nblocks; ++b) {
-        __syncthreads();                        // filter row 0 and its patch rows are in LDS
-        row(0, std::true_type{});
-        for (int r = 1; r < R; ++r) {
-            __syncthreads();                    // filter row r and the patch rows it adds are in LDS
-            row(r, std::false_type{});
-        }
-        if (b + 1 < nblocks) __syncthreads();   // the patch may be overwritten
-        epilogue(b == 0 ? tc0 : row_decode(t_begin + b, g));
+    if constexpr (SPLIT == 0) {
+        compute(std::integral_constant<int, 0>{}, std::integral_constant<int, MF>{}, std::false_type{});
+    } else {
+        if (wave < kRowWaves) compute(std::integral_constant<int, 0>{}, std::integral_constant<int, MFA>{}, std::false_type{});
+        else compute(std::integral_constant<int, MFA>{}, std::integral_constant<int, MF - MFA>{}, std::true_type{});
     }
 }
 
@@ -424,10 +455,10 @@ bool plan_row(const ConvShape& s, int MF, RowGeom* g, double* cost_out) {
     return true;
 }
 
-template <typename T, typename TO, int MF, int S_, int CPR>
+template <typename T, typename TO, int MF, int S_, int CPR, int SPLIT>
 hipError_t launch_row_t(const void* x, const void* w, void* y, const ConvShape& s, RowGeom g, hipStream_t st) {
     const int lds_bytes = g.w_bytes + g.patch_bytes + kRowWaves * kRowStage;
-    auto kern = irow_kernel<T, TO, MF, S_, CPR>;
+    auto kern = irow_kernel<T, TO, MF, S_, CPR, SPLIT>;
     const int threads = (kRowWaves + kRowLoaders) * 64;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
@@ -435,61 +466,76 @@ hipError_t launch_row_t(const void* x, const void* w, void* y, const ConvShape& 
         if (e != hipSuccess) return e;
         raised.store(true, std::memory_order_release);
     }
-    static std::atomic<long long> occ_slot{-1};
-    const int occ = cached_occupancy(occ_slot, (const void*)kern, threads, lds_bytes);
-    const int cap = call_max_workgroups();
-    const long slots = cap > 0 ? cap : (long)device_cus() * occ;
-    const long per = (g.total_tiles + slots - 1) / slots;
-    const int nwg = (int)((g.total_tiles + per - 1) / per);
+    int nwg;
+    if (SPLIT) {
+        nwg = g.total_tiles;                    // one block per workgroup: all eight waves compute, nothing is left to prefetch
+    } else {
+        static std::atomic<long long> occ_slot{-1};
+        const int occ = cached_occupancy(occ_slot, (const void*)kern, threads, lds_bytes);
+        const int cap = call_max_workgroups();
+        const long slots = cap > 0 ? cap : (long)device_cus() * occ;
+        const long per = (g.total_tiles + slots - 1) / slots;
+        nwg = (int)((g.total_tiles + per - 1) / per);
+    }
     g.tiles_base = g.total_tiles / nwg;
     g.tiles_rem = g.total_tiles % nwg;
     hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(threads), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y, s, g);
     return hipGetLastError();
 }
 
-template <int MF, int S_, int CPR>
+template <int MF, int S_, int CPR, int SPLIT>
 hipError_t launch_row_types(const void* x, const void* w, void* y, const ConvShape& s, const RowGeom& g, int in_t, int out_t,
                             hipStream_t st) {
     if (in_t == IN_BF16) {
-        if (out_t == OUT_F32) return launch_row_t<bf16_t, float, MF, S_, CPR>(x, w, y, s, g, st);
-        return launch_row_t<bf16_t, bf16_t, MF, S_, CPR>(x, w, y, s, g, st);
+        if (out_t == OUT_F32) return launch_row_t<bf16_t, float, MF, S_, CPR, SPLIT>(x, w, y, s, g, st);
+        return launch_row_t<bf16_t, bf16_t, MF, S_, CPR, SPLIT>(x, w, y, s, g, st);
     }
-    if (out_t == OUT_F32) return launch_row_t<f16_t, float, MF, S_, CPR>(x, w, y, s, g, st);
-    return launch_row_t<f16_t, f16_t, MF, S_, CPR>(x, w, y, s, g, st);
+    if (out_t == OUT_F32) return launch_row_t<f16_t, float, MF, S_, CPR, SPLIT>(x, w, y, s, g, st);
+    return launch_row_t<f16_t, f16_t, MF, S_, CPR, SPLIT>(x, w, y, s, g, st);
 }
 
-template <int MF>
+template <int MF, int SPLIT>
 hipError_t launch_row_mf(const void* x, const void* w, void* y, const ConvShape& s, const RowGeom& g, int in_t, int out_t,
                          hipStream_t st) {
     if (s.C == 64) {
-        if (s.S == 1) return launch_row_types<MF, 1, 8>(x, w, y, s, g, in_t, out_t, st);
-        return launch_row_types<MF, 3, 8>(x, w, y, s, g, in_t, out_t, st);
+        if (s.S == 1) return launch_row_types<MF, 1, 8, SPLIT>(x, w, y, s, g, in_t, out_t, st);
+        return launch_row_types<MF, 3, 8, SPLIT>(x, w, y, s, g, in_t, out_t, st);
     }
-    if (s.S == 1) return launch_row_types<MF, 1, 4>(x, w, y, s, g, in_t, out_t, st);
-    return launch_row_types<MF, 3, 4>(x, w, y, s, g, in_t, out_t, st);
+    if (s.S == 1) return launch_row_types<MF, 1, 4, SPLIT>(x, w, y, s, g, in_t, out_t, st);
+    return launch_row_types<MF, 3, 4, SPLIT>(x, w, y, s, g, in_t, out_t, st);
 }
 
-constexpr int kRowMF[] = {7, 8};
+constexpr int kRowMF[] = {7, 8, 7, 8};      // variants 0, 1: four compute + four loader waves; 2, 3: all eight compute
+
+// the all-compute form handles one block per workgroup and stages half of its output in the LDS rows of filter row 0
+bool plan_variant(const ConvShape& s, int v, RowGeom* g, double* cost) {
+    if (v < 0 || v >= 4 || !plan_row(s, kRowMF[v], g, cost)) return false;
+    return v < 2 || s.R >= 2;
+}
 
 }  // namespace
 
 bool rowres_supported(const ConvShape& s, int v) {
     RowGeom g;
-    return v >= 0 && v < 2 && plan_row(s, kRowMF[v], &g, nullptr);
+    return plan_variant(s, v, &g, nullptr);
 }
 
 bool rowres_plan_cost(const ConvShape& s, int v, double* cost, long* blocks) {
     RowGeom g;
-    if (v < 0 || v >= 2 || !plan_row(s, kRowMF[v], &g, cost)) return false;
+    if (!plan_variant(s, v, &g, cost)) return false;
     *blocks = g.total_tiles;
     return true;
 }
 
 hipError_t launch_rowres(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t st) {
     RowGeom g;
-    if (v < 0 || v >= 2 || !plan_row(s, kRowMF[v], &g, nullptr)) return hipErrorInvalidConfiguration;
-    if (v == 0) return launch_row_mf<7>(x, w, y, s, g, in_t, out_t, st);
-    return launch_row_mf<8>(x, w, y, s, g, in_t, out_t, st);
+    if (!plan_variant(s, v, &g, nullptr)) return hipErrorInvalidConfiguration;
+    switch (v) {
+        case 0: return launch_row_mf<7, 0>(x, w, y, s, g, in_t, out_t, st);
+        case 1: return launch_row_mf<8, 0>(x, w, y, s, g, in_t, out_t, st);
+        case 2: return launch_row_mf<7, 1>(x, w, y, s, g, in_t, out_t, st);
+        default: return launch_row_mf<8, 1>(x, w, y, s, g, in_t, out_t, st);
+    }
 }
 
 }  // namespace iconv

@@ -134,9 +134,10 @@ def test_kernel_choice_follows_the_layer_class(lib):
     lib.iconv_variant_name.restype = ctypes.c_char_p
     table = {lib.iconv_variant_name(i).decode() for i in range(lib.iconv_num_variants())}
     bf16 = 1
-    # the benchmark layers: resident filters (t...: phased by filter row; r...: by channel slice), per-tap
+    # the benchmark layers: resident filters (s..., t...: phased by filter row; r...: by channel slice), per-tap
     # direct-to-LDS (d...), patch reuse (p...), merged taps
-    assert kernel_for(lib, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("t448")
+    assert kernel_for(lib, 32, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("s448")          # 224 blocks: one round, all waves compute
+    assert kernel_for(lib, 64, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("t448")          # 448 blocks: persistent, loader waves
     assert kernel_for(lib, 32, 56, 56, 96, 64, 1, 1, 1, 0, 1, bf16).startswith("r")            # 96 channels: channel slices
     assert kernel_for(lib, 32, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d128x128")
     assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("a128x32")       # 1x1: pixels resident
@@ -148,7 +149,7 @@ def test_kernel_choice_follows_the_layer_class(lib):
     # tile size follows the tile count: the same layers at other batch sizes
     assert kernel_for(lib, 8, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("p128x64")      # 196 tiles of 128 pixels
     assert kernel_for(lib, 16, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("p256x64")     # 112 resident blocks: too few
-    assert kernel_for(lib, 20, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("t")           # patch tiles need two rounds
+    assert kernel_for(lib, 20, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("s")           # patch tiles need two rounds
     assert kernel_for(lib, 64, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d256x128")  # 392 tiles of 128x128
     assert kernel_for(lib, 32, 56, 56, 256, 128, 1, 1, 1, 0, 1, bf16).startswith("d256x128")  # K = 128: no 256-wide tile;
     #   four rounds of 144 KiB workgroups: not for the pixel-resident kernel, nor are 49 or 25 pixels per workgroup

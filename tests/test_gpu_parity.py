@@ -168,7 +168,8 @@ def test_workgroups_walking_several_tiles(B):
 
 def test_resident_filter_kernels(B):
     """The resident-filter kernels (filters of 64 output channels and the input patch of a block in
-    LDS), phased by channel slice ("r") or by filter row ("t"; 32 or 64 channels): all fragment counts,
+    LDS), phased by channel slice ("r") or by filter row ("t": four compute and four loader waves; "s": all eight
+    waves compute, one block per workgroup; 32 or 64 channels): all fragment counts,
     forced, on shapes with one to four channel slices, strides, dilation, ragged blocks, block widths
     with and without the skewed patch rows, tall filters and K < 64, uncapped and with workgroups
     walking through several blocks (the next block is loaded while the last one is stored)."""
@@ -185,8 +186,8 @@ def test_resident_filter_kernels(B):
               workloads.small_layer("r_k", 5, 56, 56, 64, 44, 3, 3, 1, 1, 1, seed_id=850),     # five blocks per image row group, K = 44
               workloads.small_layer("r_l", 2, 50, 56, 32, 64, 5, 3, 1, 2, 1, dtype="f16", seed_id=851)]   # five filter rows, ragged last block
     names = variant_names(B)
-    res = [v for v, nm in enumerate(names) if nm[0] in "rt"]
-    assert len(res) == 4
+    res = [v for v, nm in enumerate(names) if nm[0] in "rts"]
+    assert len(res) == 6
     ran = 0
     for cap in (0, 1, 3):
         for v in res:
@@ -290,7 +291,8 @@ def test_sixteen_bit_output_within_one_ulp(B, dtype):
 
 
 # (case name, kernel-table entry forced ("" = the library's choice), workgroup cap, layer): one per epilogue that
-# converts to a 16-bit type -- resident-filter (staged, 7 and 8 fragments), per-tap with staged whole-line stores
+# converts to a 16-bit type -- resident-filter (staged, 7 and 8 fragments, loader-wave and all-compute forms), pixel-resident
+# 1x1, per-tap with staged whole-line stores
 # (K % 4 == 0) and with the direct / scalar-tail stores (K % 4 != 0), per-tap prefetching, patch-reuse direct
 # (several tiles per workgroup) and last-tile staged, patch-reuse drained by store waves, prefetching patch-reuse,
 # merged-tap stem, plain direct kernel.
@@ -301,6 +303,10 @@ OUT16_CASES = [
     ("row_f7", "t448x64", 0, ("o_t7", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1)),
     ("row_f7_walk_c32", "t448x64", 2, ("o_t7w", 3, 28, 28, 32, 48, 3, 3, 1, 1, 1)),
     ("row_f8_1x1", "t512x64", 0, ("o_t8", 2, 32, 32, 64, 64, 1, 1, 1, 0, 1)),
+    ("split_f7", "s448x64", 0, ("o_s7", 4, 56, 56, 64, 64, 3, 3, 1, 1, 1)),
+    ("split_f7_c32_k48", "s448x64", 0, ("o_s7c", 3, 28, 28, 32, 48, 3, 3, 1, 1, 1)),
+    ("split_f8_3x1", "s512x64", 0, ("o_s8", 2, 32, 32, 64, 60, 3, 1, 1, 1, 1)),
+    ("pixel_resident_1x1", "a128x32", 0, ("o_a1", 3, 13, 9, 128, 200, 1, 1, 2, 0, 1)),
     ("tap_256x256x32_staged", "d256x256x32", 0, ("o_t4", 2, 28, 28, 72, 264, 1, 1, 2, 0, 1)),
     ("tap_128x128_pf_staged", "d128x128x64_w64x32_s3_pf", 0, ("o_t8", 2, 30, 30, 128, 160, 3, 3, 2, 1, 1)),
     ("tap_128x64_scalar_tail", "d128x64x64", 0, ("o_t2", 2, 15, 17, 32, 42, 3, 3, 2, 1, 1)),
