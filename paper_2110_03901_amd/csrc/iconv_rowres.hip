@@ -21,7 +21,12 @@
 //    groups of a patch row.
 //
 // Waves: four compute waves (pixel half x filter half, MF accumulator tiles of 32x32, as in
-// iconv_resident.hip) and four loader waves.  LDS: [filters: tap x 64 filters x 2C bytes]
+// iconv_resident.hip) and four loader waves, persistent over a range of blocks (the next block is
+// loaded under the stores of the current one) -- or, for launches with one block per workgroup
+// (SPLIT), eight waves that all compute: the four that issue the later phases take the last MF/2
+// fragments of their (pixel half, filter half), so that every SIMD has two waves issuing MFMAs and
+// each hides the other's operand reads and address arithmetic (19-20 ns -> about 17.5 ns per MFMA).
+// LDS: [filters: tap x 64 filters x 2C bytes]
 // [patch: PH rows x PWp pixels x 2C bytes][staging: 2 KiB per compute wave].  Chunk c (16 bytes) of
 // row i is stored at chunk  c ^ swz(i),  swz(i) = (i >> 1) & 7 for 128-byte rows, (i >> 2) & 3 for
 // 64-byte rows: the 16 lanes the LDS serves in one pass of a ds_read_b128 (lanes 0-3, 12-15, 20-27 or
