@@ -354,6 +354,21 @@ def test_benchmark_layer_at_batch_64(B, name):
     check(B, workloads.with_batch(workloads.LAYERS[name], 64))
 
 
+def test_headline_layer_through_both_row_phased_forms(B):
+    """cfg2 at full size through the form the library does NOT choose for it as well: the persistent one (loader waves)
+    at batch 32, where every workgroup has a single block, and the all-compute one at batch 64, where the 448
+    workgroups come in two rounds."""
+    names = variant_names(B)
+    t = [i for i, nm in enumerate(names) if nm.startswith("t448")][0]
+    s_ = [i for i, nm in enumerate(names) if nm.startswith("s448")][0]
+    L = workloads.LAYERS["cfg2"]
+    assert B.iconv_kernel_for(*L.shape_args(), code_of(L)).startswith("s448")
+    check(B, L, variant=t)
+    L64 = workloads.with_batch(L, 64)
+    assert B.iconv_kernel_for(*L64.shape_args(), code_of(L64)).startswith("t448")
+    check(B, L64, variant=s_)
+
+
 # ---- explicit variant ------------------------------------------------------------------------
 
 EXPLICIT = ["tile_tail", "c24_partial_chunk", "stride2", "stride3_dil2", "big_pad", "direct_c3", "stem_c4"]
