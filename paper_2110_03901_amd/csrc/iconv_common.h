@@ -89,10 +89,12 @@ bool rowres_plan_cost(const ConvShape& s, int v, double* cost, long* blocks);
 hipError_t launch_rowres(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t stream);
 
 // Pixel-resident kernel for 1x1 layers (C = 64, 128 or 256; K % 4 == 0): a workgroup keeps its pixels in LDS and
-// streams the filters, two teams of compute waves alternating between MFMAs and stores.
+// streams the filters through two teams of compute waves; variant 0: the compute waves store, 1: store waves do.
 bool pointwise_supported(const ConvShape& s);
-bool pointwise_preferred(const ConvShape& s);   // supported, and measured faster than the per-tap kernels on such layers
-hipError_t launch_pointwise(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t stream);
+int pointwise_choose(const ConvShape& s);       // the form measured fastest on such layers, or -1: a per-tap kernel is faster
+int pointwise_num_variants();
+const char* pointwise_variant_name(int v);
+hipError_t launch_pointwise(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t stream);
 
 // Merged-tap kernel for C == 4 first layers (stride 2, dilation 1, even W, S + (pad & 1) <= 8).
 bool stem_supported(const ConvShape& s);

@@ -380,7 +380,8 @@ int choose_variant(const ConvShape& s) {
         if (v != kP64x128 && s.K > 64 && patch_supported(s, kP64x128)) return P0 + kP64x128;
     }
     if (s.R * s.S == 1) {
-        if (pointwise_preferred(s)) return pointwise_index();
+        const int pv = pointwise_choose(s);
+        if (pv >= 0) return pointwise_index() + pv;
         const long tiles_256x256 = (long)((s.M + 255) / 256) * ((s.K + 255) / 256);
         if (s.K > 128 && tiles_256x256 >= 160) return kD256x256;
         if (tiles_256x128 >= 160) return kD256x128;
@@ -398,13 +399,13 @@ int choose_variant(const ConvShape& s) {
 }  // namespace
 
 // Variant numbering seen through the C ABI: the per-tap kernels of this file first, then the
-// patch-reuse kernels, then the resident-filter kernels, then the pixel-resident 1x1 kernel.
-int mfma_num_variants() { return kNumVariants + patch_num_variants() + resident_num_variants() + 1; }
+// patch-reuse kernels, then the resident-filter kernels, then the pixel-resident 1x1 kernels.
+int mfma_num_variants() { return pointwise_index() + pointwise_num_variants(); }
 const char* mfma_variant_name(int v) {
     if (v < kNumVariants) return kVariantNames[v];
     if (v < kNumVariants + patch_num_variants()) return patch_variant_name(v - kNumVariants);
     if (v < pointwise_index()) return resident_variant_name(v - kNumVariants - patch_num_variants());
-    return "a128x32_2x4+8";
+    return pointwise_variant_name(v - pointwise_index());
 }
 
 int mfma_default_variant(const ConvShape& s) { return choose_variant(s); }
@@ -412,7 +413,7 @@ int mfma_default_variant(const ConvShape& s) { return choose_variant(s); }
 bool mfma_variant_accepts(const ConvShape& s, int v) {
     const int R0 = kNumVariants + patch_num_variants();
     if (v < 0 || v >= mfma_num_variants()) return false;
-    if (v == pointwise_index()) return pointwise_supported(s);
+    if (v >= pointwise_index()) return pointwise_supported(s);
     if (v >= R0) return resident_supported(s, v - R0);
     if (v >= kNumVariants) return patch_supported(s, v - kNumVariants);
     return true;
@@ -422,14 +423,14 @@ hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s
                        hipStream_t st) {
     const int R0 = kNumVariants + patch_num_variants();        // first resident-filter variant
     const int A0 = pointwise_index();
-    if (variant == A0 && pointwise_supported(s)) return launch_pointwise(x, w, y, s, in_t, out_t, st);
+    if (variant >= A0 && variant < mfma_num_variants() && pointwise_supported(s)) return launch_pointwise(x, w, y, s, in_t, out_t, variant - A0, st);
     if (variant >= R0 && variant < A0 && resident_supported(s, variant - R0))
         return launch_resident(x, w, y, s, in_t, out_t, variant - R0, st);
     if (variant >= kNumVariants && variant < R0 && patch_supported(s, variant - kNumVariants))
         return launch_patch(x, w, y, s, in_t, out_t, variant - kNumVariants, st);
     int v = variant;
     if (v < 0 || v >= kNumVariants) v = choose_variant(s);    // also when a forced kernel does not fit the layer
-    if (v == A0) return launch_pointwise(x, w, y, s, in_t, out_t, st);
+    if (v >= A0) return launch_pointwise(x, w, y, s, in_t, out_t, v - A0, st);
     if (v >= R0) return launch_resident(x, w, y, s, in_t, out_t, v - R0, st);
     if (v >= kNumVariants) return launch_patch(x, w, y, s, in_t, out_t, v - kNumVariants, st);
     if (in_t == IN_BF16) {

@@ -237,6 +237,241 @@ ipw_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y,
     }
 }
 
+// The same kernel with STORE WAVES: 2 teams x 4 compute waves, 4 loader waves and 4 store waves.  A wave that stores
+// is held until the memory system has taken its data, and on this layer type the write of y is what takes
+// longest, so here the compute waves never store: they deposit their fragments in one of two staging areas in
+// LDS (each two tiles of 128 pixels x 32 filters in fp32, the layout of stage_off), and in the next tick the
+// store waves carry that area out while the compute waves fill the other one.  One barrier per tick: it says
+// that the tiles of the next pair have landed, that the staging area of this tick is complete and that the
+// one of the last tick has been read.  The store waves finish with one more round after the last tick.
+//
+// LDS: [pixels][filter slots outside the pixel region][2 staging areas of 32 KiB].  The ring has eight slots
+// (four pairs) up to 128 channels and six (three pairs) at 256, where four slots are the pixel region;
+// the pixel region becomes slots once every compute wave has its pixel fragments in registers, which a
+// barrier of its own announces.
+constexpr int kPwsLoaders = 4;
+constexpr int kPwsStaging = 2 * kPwBM * 128;      // bytes of one staging area: two tiles x 128 pixels x 32 fp32 outputs
+
+template <int CPR> struct PwsLayout {
+    static constexpr int SLOTS = CPR == 32 ? 6 : 8;
+    static constexpr int OUTSIDE = SLOTS - 4;               // slots that are not the pixel region
+    static constexpr int A_BYTES = kPwBM * CPR * 16, B_BYTES = kPwBN * CPR * 16;
+    static constexpr int STG = A_BYTES + OUTSIDE * B_BYTES; // byte offset of the staging areas
+    static constexpr int LDS_BYTES = STG + 2 * kPwsStaging;
+    static_assert(4 * B_BYTES <= A_BYTES && LDS_BYTES <= 160 * 1024, "LDS of a compute unit");
+    __device__ static uint32_t slot(int s) {
+        return s < OUTSIDE ? (uint32_t)(A_BYTES + s * B_BYTES) : (uint32_t)((s - OUTSIDE) * B_BYTES);
+    }
+};
+
+template <typename T, typename TO, int CPR>
+__global__ void __launch_bounds__(kPwWaves * 64)
+ipws_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const PwGeom g) {
+    static_assert(CPR == 8 || CPR == 16 || CPR == 32, "64, 128 or 256 channels");
+    typedef typename Elem<T>::frag frag_t;
+    typedef PwsLayout<CPR> LY;
+    constexpr int PITCH = CPR * 16;
+    constexpr int RPI = 64 / CPR;
+    constexpr int NA = kPwBM / RPI;
+    constexpr int NB = kPwBN / RPI;
+    constexpr int KK = CPR / 2;
+    constexpr int A_BYTES = LY::A_BYTES;
+    constexpr int LPT = (NB + kPwsLoaders - 1) / kPwsLoaders;
+    constexpr int NPAIR = LY::SLOTS / 2;                    // pairs of tiles in the ring
+
+    extern __shared__ u32x4 lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)lds;
+
+    const int m0 = blockIdx.x * g.rows_per_wg;
+    const int rows = min(g.rows_per_wg, s.M - m0);
+    const int n0 = m0 / s.PQ;
+    const int rem0 = m0 - n0 * s.PQ;
+    const int p0 = rem0 / s.Q;
+    const int q0 = rem0 - p0 * s.Q;
+
+    const size_t x_off = (size_t)n0 * s.H * s.W * s.C;
+    const size_t x_rem = ((size_t)s.N * s.H * s.W * s.C - x_off) * 2u;
+    const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x) + x_off, 0, x_rem > kPwDrop ? kPwDrop : (uint32_t)x_rem,
+                                                           kRsrcFlags);
+    const uint32_t w_bytes = (uint32_t)s.K * s.C * 2u;
+    const rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(w), 0, w_bytes, kRsrcFlags);
+
+    const int r_in = lane / CPR, pc = lane % CPR;
+    auto a_offset = [&](int row) -> uint32_t {
+        const int lc = swz<CPR>(row, pc);
+        const int qq = q0 + row;
+        const int dp = (int)(((float)qq + 0.5f) * g.inv_q);
+        const int q = qq - dp * s.Q;
+        const int pp = p0 + dp;
+        const int dn = (int)(((float)pp + 0.5f) * g.inv_p);
+        const int p = pp - dn * s.P;
+        const int h = p * s.stride - s.pad, ww = q * s.stride - s.pad;
+        const bool ok = row < rows && (unsigned)h < (unsigned)s.H && (unsigned)ww < (unsigned)s.W;
+        return ok ? (uint32_t)(((dn * s.H + h) * s.W + ww) * s.C + lc * 8) * 2u : kPwDrop;
+    };
+    auto b_offset = [&](int tile, int row) -> uint32_t {
+        const int lc = swz<CPR>(row, pc);
+        const int k = tile * kPwBN + row;
+        return k < s.K ? (uint32_t)(k * s.C + lc * 8) * 2u : kPwDrop;
+    };
+
+    // ---- phase 0: the pixels and filter tiles 0 and 1 (slots 0 and 1), one share per wave (all sixteen issue)
+#pragma unroll
+    for (int i = 0; i < (NA + 2 * NB + kPwWaves - 1) / kPwWaves; ++i) {
+        const int j = wave + i * kPwWaves;
+        if (j < NA) {
+            dma16(x_rsrc, a_offset(j * RPI + r_in), lds_base + (uint32_t)j * 1024u);
+        } else if (j < NA + 2 * NB) {
+            const int jb = j - NA;
+            dma16(w_rsrc, b_offset(jb / NB, (jb % NB) * RPI + r_in), lds_base + A_BYTES + (uint32_t)jb * 1024u);
+        }
+    }
+
+    const int NT = g.tiles_n;
+    const int NP = (NT + 1) / 2;
+    // Every role passes the same barriers: phase 0 landed, pixel fragments taken, then one per tick.
+    if (wave >= 12) {
+        // =========================== store waves ============================================
+        const int sw = wave - 12;                           // pixels 32 sw .. 32 sw + 31 of both tiles
+        const int l8 = lane >> 3, c8 = lane & 7;
+        const size_t y_off = (size_t)m0 * s.K;
+        const size_t y_rem = ((size_t)s.M * s.K - y_off) * sizeof(TO);
+        const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + y_off, 0, y_rem > kPwDrop ? kPwDrop : (uint32_t)y_rem, kRsrcFlags);
+        const char* stg = reinterpret_cast<const char*>(lds) + LY::STG;
+        uint32_t rd[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rd[i] = stage_off(sw * 32 + i * 8 + l8, c8);
+        wait_vmcnt<0>();
+        __syncthreads();
+        __syncthreads();
+        for (int j = 0; j <= NP; ++j) {
+            if (j > 0) {                                    // the outputs of tick j - 1
+                const char* area = stg + ((j - 1) & 1) * kPwsStaging;
+                u32x4 v[2][4];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[t][i] = *reinterpret_cast<const u32x4*>(area + t * (kPwsStaging / 2) + rd[i]);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int tile = 2 * (j - 1) + t;
+                    const int k_first = tile * kPwBN;
+                    const bool pieces_ok = tile < NT && k_first + 4 * c8 + 3 < s.K;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int row = sw * 32 + i * 8 + l8;
+                        if (sw * 32 + i * 8 < rows) {       // uniform: some pixel of the instruction exists
+                            const uint32_t ro = row < rows ? (uint32_t)(row * s.K + k_first + 4 * c8) * (uint32_t)sizeof(TO) : kPwDrop;
+                            if (pieces_ok) store_piece<TO>(v[t][i], y_rsrc, ro);
+                        }
+                    }
+                }
+            }
+            if (j < NP) __syncthreads();
+        }
+        return;
+    }
+    if (wave >= 8) {
+        // =========================== loader waves ===========================================
+        const int lw = wave - 8;
+        auto request = [&](int tile) {
+            if (tile >= NT) return;
+            const uint32_t slot = lds_base + LY::slot(tile % LY::SLOTS);
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                const int j = lw + i * kPwsLoaders;
+                if (j < NB) dma16(w_rsrc, b_offset(tile, j * RPI + r_in), slot + (uint32_t)j * 1024u);
+            }
+        };
+        auto request_pair = [&](int p) {
+            request(2 * p);
+            request(2 * p + 1);
+        };
+        const bool issues = lw < NB;
+        // Loads complete in order within a wave: with at most the loads of the `after` tiles requested last
+        // outstanding, everything requested before them has landed.
+        auto landed_but = [&](int after) {
+            if (!issues || after <= 0) wait_vmcnt<0>();
+            else if (after == 1) wait_vmcnt<LPT>();
+            else if (after == 2) wait_vmcnt<2 * LPT>();
+            else if (after == 3) wait_vmcnt<3 * LPT>();
+            else wait_vmcnt<4 * LPT>();
+        };
+        auto tiles_in = [&](int first, int last) { return max(0, min(NT - 1, last) - first + 1); };
+        wait_vmcnt<0>();
+        __syncthreads();                                    // phase 0 has landed
+        __syncthreads();                                    // the pixel region is free
+        for (int p = 1; p < NPAIR; ++p) request_pair(p);
+        for (int j = 0; j < NP; ++j) {
+            // Tick j works on pair j; pair j + 1 must have landed when it ends.  Pair j + NPAIR - 1 takes the slots
+            // of pair j - 1, which every compute wave has left at the last barrier.
+            if (j >= 1) request_pair(j + NPAIR - 1);
+            landed_but(tiles_in(2 * (j + 2), 2 * (j + NPAIR - 1) + 1));
+            __syncthreads();
+        }
+        return;
+    }
+
+    // =========================== compute waves ==============================================
+    const int team = wave >> 2;
+    const int wq = wave & 3;
+    const int frow = lane & 31, fk = lane >> 5;
+    const char* lds_b = reinterpret_cast<const char*>(lds);
+    const int arow = wq * 32 + frow;
+    const uint32_t a_base = (uint32_t)(arow * PITCH + (swz<CPR>(arow, fk) << 4));
+    const uint32_t b_base = (uint32_t)(frow * PITCH + (swz<CPR>(frow, fk) << 4));
+    char* dep = reinterpret_cast<char*>(lds) + LY::STG + team * (kPwsStaging / 2);
+    const uint32_t dep0 = stage_off(arow, fk);
+
+    floatx16 acc;
+    frag_t areg[KK];
+    // Filter fragments are read two K slices ahead.
+    auto multiply = [&](int slot) {
+        const char* pb = lds_b + LY::slot(slot);
+        constexpr int AHEAD = 2;
+        frag_t b[AHEAD];
+#pragma unroll
+        for (int kk = 0; kk < AHEAD; ++kk) b[kk] = *reinterpret_cast<const frag_t*>(pb + (b_base ^ (uint32_t)(kk << 5)));
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk == 0) {
+                floatx16 z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                acc = Elem<T>::mfma32(b[kk % AHEAD], areg[kk], z);
+            } else {
+                acc = Elem<T>::mfma32(b[kk % AHEAD], areg[kk], acc);
+            }
+            if (kk + AHEAD < KK)
+                b[kk % AHEAD] = *reinterpret_cast<const frag_t*>(pb + (b_base ^ (uint32_t)((kk + AHEAD) << 5)));
+        }
+    };
+
+    wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) areg[kk] = *reinterpret_cast<const frag_t*>(lds_b + (a_base ^ (uint32_t)(kk << 5)));
+    __syncthreads();                                        // (waits for the reads above)
+    for (int j = 0; j < NP; ++j) {
+        const int tile = 2 * j + team;
+        if (tile < NT) {
+            multiply(tile % LY::SLOTS);
+            // lane l holds pixel l%32 of the wave's fragment and, in element v, filter 8*(v/4) + 4*(l/32) + v%4:
+            // piece 2*(v/4) + l/32 of the pixel's staging row, i.e. the lane's address xor (v/4 << 5)
+            char* area = dep + (j & 1) * kPwsStaging;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                floatx4 v = {acc[4 * gq], acc[4 * gq + 1], acc[4 * gq + 2], acc[4 * gq + 3]};
+                *reinterpret_cast<floatx4*>(area + (dep0 ^ (uint32_t)(gq << 5))) = v;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 bool plan_pw(const ConvShape& s, PwGeom* g) {
     if (s.R != 1 || s.S != 1) return false;
     if (s.C != 64 && s.C != 128 && s.C != 256) return false;
@@ -258,10 +493,12 @@ bool plan_pw(const ConvShape& s, PwGeom* g) {
     return true;
 }
 
-template <typename T, typename TO, int CPR>
+template <typename T, typename TO, int CPR, int FORM>
 hipError_t launch_pw_t(const void* x, const void* w, void* y, const ConvShape& s, const PwGeom& g, hipStream_t st) {
-    constexpr int lds_bytes = (kPwBM + 4 * kPwBN) * CPR * 16 + 8 * kPwStage;
-    auto kern = ipw_kernel<T, TO, CPR>;
+    // FORM 0: staging of 2 KiB per compute wave; FORM 1: two staging areas for the store waves
+    constexpr int lds_bytes = FORM == 0 ? (kPwBM + 4 * kPwBN) * CPR * 16 + 8 * kPwStage : PwsLayout<CPR>::LDS_BYTES;
+    static_assert(lds_bytes <= 160 * 1024, "LDS of a compute unit");
+    auto kern = FORM == 0 ? ipw_kernel<T, TO, CPR> : ipws_kernel<T, TO, CPR>;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -273,15 +510,30 @@ hipError_t launch_pw_t(const void* x, const void* w, void* y, const ConvShape& s
     return hipGetLastError();
 }
 
-template <typename T, typename TO>
+template <typename T, typename TO, int FORM>
 hipError_t launch_pw_c(const void* x, const void* w, void* y, const ConvShape& s, const PwGeom& g, hipStream_t st) {
     switch (s.C) {
-        case 64: return launch_pw_t<T, TO, 8>(x, w, y, s, g, st);
-        case 128: return launch_pw_t<T, TO, 16>(x, w, y, s, g, st);
-        case 256: return launch_pw_t<T, TO, 32>(x, w, y, s, g, st);
+        case 64: return launch_pw_t<T, TO, 8, FORM>(x, w, y, s, g, st);
+        case 128: return launch_pw_t<T, TO, 16, FORM>(x, w, y, s, g, st);
+        case 256: return launch_pw_t<T, TO, 32, FORM>(x, w, y, s, g, st);
         default: return hipErrorInvalidConfiguration;
     }
 }
+
+template <int FORM>
+hipError_t launch_pw_f(const void* x, const void* w, void* y, const ConvShape& s, const PwGeom& g, int in_t, int out_t, hipStream_t st) {
+    if (in_t == IN_BF16) {
+        if (out_t == OUT_F32) return launch_pw_c<bf16_t, float, FORM>(x, w, y, s, g, st);
+        if (out_t == OUT_BF16) return launch_pw_c<bf16_t, bf16_t, FORM>(x, w, y, s, g, st);
+    } else if (in_t == IN_F16) {
+        if (out_t == OUT_F32) return launch_pw_c<f16_t, float, FORM>(x, w, y, s, g, st);
+        if (out_t == OUT_F16) return launch_pw_c<f16_t, f16_t, FORM>(x, w, y, s, g, st);
+    }
+    return hipErrorInvalidConfiguration;
+}
+
+const char* const kPwNames[] = {"a128x32_2x4+8", "a128x32_2x4+4+4"};
+constexpr int kNumPw = 2;
 
 }  // namespace
 
@@ -293,25 +545,27 @@ bool pointwise_supported(const ConvShape& s) {
 // Where it measured faster than the per-tap kernels: workgroups with (nearly) full pixel tiles -- the MFMAs always
 // run on 128 rows, and every workgroup streams all filters -- that either run as one round over the compute units
 // or are small enough (128 channels or fewer) for several to share a compute unit, so that one workgroup's start-up
-// hides behind another's stores.
-bool pointwise_preferred(const ConvShape& s) {
+// hides behind another's stores.  The form with store waves wins where a workgroup has many filter tiles to write
+// (256 filters or more) and 128 or 256 channels (-3 to -11 %); with few tiles its longer start and end cost more
+// than the overlap gains, and at 64 channels three workgroups of the first form share a compute unit.
+// Returns the variant (0: compute waves store, 1: store waves) or -1.
+int pointwise_choose(const ConvShape& s) {
     PwGeom g;
-    if (!plan_pw(s, &g) || g.rows_per_wg < 96) return false;
+    if (!plan_pw(s, &g) || g.rows_per_wg < 96) return -1;
     const long nwg = (s.M + g.rows_per_wg - 1) / g.rows_per_wg;
-    return nwg <= device_cus() || s.C <= 128;
+    if (nwg > device_cus() && s.C > 128) return -1;
+    return s.C >= 128 && g.tiles_n >= 8 ? 1 : 0;
 }
 
-hipError_t launch_pointwise(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t st) {
+int pointwise_num_variants() { return kNumPw; }
+const char* pointwise_variant_name(int v) { return kPwNames[v]; }
+
+hipError_t launch_pointwise(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t st) {
     PwGeom g;
     if (!plan_pw(s, &g)) return hipErrorInvalidConfiguration;
-    if (in_t == IN_BF16) {
-        if (out_t == OUT_F32) return launch_pw_c<bf16_t, float>(x, w, y, s, g, st);
-        if (out_t == OUT_BF16) return launch_pw_c<bf16_t, bf16_t>(x, w, y, s, g, st);
-    } else if (in_t == IN_F16) {
-        if (out_t == OUT_F32) return launch_pw_c<f16_t, float>(x, w, y, s, g, st);
-        if (out_t == OUT_F16) return launch_pw_c<f16_t, f16_t>(x, w, y, s, g, st);
-    }
-    return hipErrorInvalidConfiguration;
+    if (v == 0) return launch_pw_f<0>(x, w, y, s, g, in_t, out_t, st);
+    if (v == 1) return launch_pw_f<1>(x, w, y, s, g, in_t, out_t, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace iconv

@@ -215,18 +215,19 @@ def test_pixel_resident_kernel_for_1x1_layers(B):
               workloads.small_layer("a_g", 9, 64, 64, 128, 96, 1, 1, 1, 0, 1, seed_id=866),     # two rounds of workgroups of 72 pixels
               workloads.small_layer("a_h", 1, 40, 33, 128, 320, 1, 1, 3, 0, 1, dtype="f16", seed_id=867)]  # stride 3, five tiles
     names = variant_names(B)
-    v = [i for i, nm in enumerate(names) if nm.startswith("a128")]
-    assert len(v) == 1
-    for L in shapes:
-        assert B.iconv_variant_accepts(v[0], *L.shape_args(), code_of(L)), L.name
-        print("pixel-resident", L.name, flush=True)
-        check(B, L, variant=v[0])
-    for L in (shapes[1], shapes[3], shapes[7]):
-        print("pixel-resident 16-bit out", L.name, flush=True)
-        check_sixteen_bit(B, L, variant=v[0])
+    forms = [i for i, nm in enumerate(names) if nm.startswith("a128")]
+    assert len(forms) == 2                                                                     # compute waves store / store waves
     not_for_it = workloads.small_layer("a_x", 1, 9, 9, 96, 64, 1, 1, 1, 0, 1, seed_id=868)       # 96 channels
-    assert not B.iconv_variant_accepts(v[0], *not_for_it.shape_args(), code_of(not_for_it))
-    check(B, not_for_it, variant=v[0])                                                         # falls back, still the convolution
+    for v in forms:
+        for L in shapes:
+            assert B.iconv_variant_accepts(v, *L.shape_args(), code_of(L)), L.name
+            print("pixel-resident", names[v], L.name, flush=True)
+            check(B, L, variant=v)
+        for L in (shapes[1], shapes[3], shapes[7]):
+            print("pixel-resident 16-bit out", names[v], L.name, flush=True)
+            check_sixteen_bit(B, L, variant=v)
+        assert not B.iconv_variant_accepts(v, *not_for_it.shape_args(), code_of(not_for_it))
+        check(B, not_for_it, variant=v)                                                        # falls back, still the convolution
 
 
 def test_merged_tap_workgroups_walking_several_blocks(B):
