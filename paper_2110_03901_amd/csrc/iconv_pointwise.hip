@@ -335,38 +335,36 @@ ipws_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     // Every role passes the same barriers: phase 0 landed, pixel fragments taken, then one per tick.
     if (wave >= 12) {
         // =========================== store waves ============================================
-        const int sw = wave - 12;                           // pixels 32 sw .. 32 sw + 31 of both tiles
+        // Store wave sw carries tile sw % 2 of the pair: the groups of eight pixels 2k + sw / 2, k = 0 .. 7 (with fewer
+        // than 128 pixels in the workgroup the existing groups are then spread evenly over the four waves).
+        const int sw = wave - 12;
+        const int st = sw & 1, g0 = sw >> 1;
         const int l8 = lane >> 3, c8 = lane & 7;
         const size_t y_off = (size_t)m0 * s.K;
         const size_t y_rem = ((size_t)s.M * s.K - y_off) * sizeof(TO);
         const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + y_off, 0, y_rem > kPwDrop ? kPwDrop : (uint32_t)y_rem, kRsrcFlags);
-        const char* stg = reinterpret_cast<const char*>(lds) + LY::STG;
-        uint32_t rd[4];
+        const char* stg = reinterpret_cast<const char*>(lds) + LY::STG + st * (kPwsStaging / 2);
+        uint32_t rd[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rd[i] = stage_off(sw * 32 + i * 8 + l8, c8);
+        for (int i = 0; i < 8; ++i) rd[i] = stage_off((2 * i + g0) * 8 + l8, c8);
         wait_vmcnt<0>();
         __syncthreads();
         __syncthreads();
         for (int j = 0; j <= NP; ++j) {
             if (j > 0) {                                    // the outputs of tick j - 1
                 const char* area = stg + ((j - 1) & 1) * kPwsStaging;
-                u32x4 v[2][4];
+                u32x4 v[8];
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
+                for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const u32x4*>(area + rd[i]);
+                const int tile = 2 * (j - 1) + st;
+                const int k_first = tile * kPwBN;
+                const bool pieces_ok = tile < NT && k_first + 4 * c8 + 3 < s.K;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) v[t][i] = *reinterpret_cast<const u32x4*>(area + t * (kPwsStaging / 2) + rd[i]);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int tile = 2 * (j - 1) + t;
-                    const int k_first = tile * kPwBN;
-                    const bool pieces_ok = tile < NT && k_first + 4 * c8 + 3 < s.K;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int row = sw * 32 + i * 8 + l8;
-                        if (sw * 32 + i * 8 < rows) {       // uniform: some pixel of the instruction exists
-                            const uint32_t ro = row < rows ? (uint32_t)(row * s.K + k_first + 4 * c8) * (uint32_t)sizeof(TO) : kPwDrop;
-                            if (pieces_ok) store_piece<TO>(v[t][i], y_rsrc, ro);
-                        }
+                for (int i = 0; i < 8; ++i) {
+                    const int row = (2 * i + g0) * 8 + l8;
+                    if ((2 * i + g0) * 8 < rows) {          // uniform: some pixel of the instruction exists
+                        const uint32_t ro = row < rows ? (uint32_t)(row * s.K + k_first + 4 * c8) * (uint32_t)sizeof(TO) : kPwDrop;
+                        if (pieces_ok) store_piece<TO>(v[i], y_rsrc, ro);
                     }
                 }
             }
@@ -542,19 +540,25 @@ bool pointwise_supported(const ConvShape& s) {
     return plan_pw(s, &g);
 }
 
-// Where it measured faster than the per-tap kernels: workgroups with (nearly) full pixel tiles -- the MFMAs always
-// run on 128 rows, and every workgroup streams all filters -- that either run as one round over the compute units
-// or are small enough (128 channels or fewer) for several to share a compute unit, so that one workgroup's start-up
-// hides behind another's stores.  The form with store waves wins where a workgroup has many filter tiles to write
-// (256 filters or more) and 128 or 256 channels (-3 to -11 %); with few tiles its longer start and end cost more
-// than the overlap gains, and at 64 channels three workgroups of the first form share a compute unit.
+// Where these kernels measured faster than the per-tap kernels (28x28 and 56x56 maps, 64 to 256 channels, 128 to
+// 1024 filters, batch 16 to 128).  The MFMAs always run on 128 rows and every workgroup streams all filters, so a
+// workgroup needs enough pixels: 96 of 128 for the first form, 64 for the form with store waves, which loses less
+// when the tile is not full (its stores, not its MFMAs, set the pace).  With 128 or 256 channels the form with
+// store waves is the faster of the two (-3 to -12 %) unless a workgroup writes only four tiles and there are
+// several rounds of workgroups; at 64 channels three workgroups of the first form share a compute unit, which
+// overlaps as much.  With 256 channels a workgroup fills the LDS of a compute unit, and in several rounds the
+// per-tap kernel with 256 x 256 tiles is faster up to 256 filters.
 // Returns the variant (0: compute waves store, 1: store waves) or -1.
 int pointwise_choose(const ConvShape& s) {
     PwGeom g;
-    if (!plan_pw(s, &g) || g.rows_per_wg < 96) return -1;
+    if (!plan_pw(s, &g)) return -1;
     const long nwg = (s.M + g.rows_per_wg - 1) / g.rows_per_wg;
-    if (nwg > device_cus() && s.C > 128) return -1;
-    return s.C >= 128 && g.tiles_n >= 8 ? 1 : 0;
+    const bool one_round = nwg <= device_cus();
+    if (s.C == 64) return g.rows_per_wg >= 96 ? 0 : -1;
+    if (g.rows_per_wg < 64) return -1;
+    if (one_round) return 1;
+    if (s.C == 128) return s.K >= 256 ? 1 : (g.rows_per_wg >= 96 ? 0 : -1);
+    return s.K >= 512 ? 1 : -1;
 }
 
 int pointwise_num_variants() { return kNumPw; }

@@ -140,7 +140,7 @@ def test_kernel_choice_follows_the_layer_class(lib):
     assert kernel_for(lib, 64, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("t448")          # 448 blocks: persistent, loader waves
     assert kernel_for(lib, 32, 56, 56, 96, 64, 1, 1, 1, 0, 1, bf16).startswith("r")            # 96 channels: channel slices
     assert kernel_for(lib, 32, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d128x128")
-    assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("a128x32")       # 1x1: pixels resident
+    assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16) == "a128x32_2x4+4+4"        # 1x1: pixels resident, store waves
     assert kernel_for(lib, 8, 64, 64, 256, 256, 3, 3, 1, 2, 2, bf16).startswith("p256x128")
     assert kernel_for(lib, 64, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16).startswith("p64x128_c128")
     assert kernel_for(lib, 64, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem"
@@ -152,10 +152,15 @@ def test_kernel_choice_follows_the_layer_class(lib):
     assert kernel_for(lib, 20, 56, 56, 64, 64, 3, 3, 1, 1, 1, bf16).startswith("s")           # patch tiles need two rounds
     assert kernel_for(lib, 64, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d256x128")  # 392 tiles of 128x128
     assert kernel_for(lib, 32, 56, 56, 256, 128, 1, 1, 1, 0, 1, bf16).startswith("d256x128")  # K = 128: no 256-wide tile;
-    #   four rounds of 144 KiB workgroups: not for the pixel-resident kernel, nor are 49 or 25 pixels per workgroup
-    assert kernel_for(lib, 64, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("d256x256")
+    #   several rounds of workgroups that fill a compute unit's LDS and write four tiles each: not for the pixel-resident
+    #   kernels, nor are 49 pixels per workgroup; with 16 tiles to write, or 74 pixels, the form with store waves
+    assert kernel_for(lib, 64, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16) == "a128x32_2x4+4+4"
+    assert kernel_for(lib, 64, 56, 56, 256, 256, 1, 1, 2, 0, 1, bf16).startswith("d256x256")
     assert kernel_for(lib, 16, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("d")
-    assert kernel_for(lib, 32, 56, 56, 64, 256, 1, 1, 1, 0, 1, bf16).startswith("a128x32")    # 64 channels: several per compute unit
+    assert kernel_for(lib, 24, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16) == "a128x32_2x4+4+4"
+    assert kernel_for(lib, 32, 56, 56, 64, 256, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+8"       # 64 channels: several per compute unit
+    assert kernel_for(lib, 32, 28, 28, 128, 512, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+4+4"    # 16 filter tiles per workgroup: store waves
+    assert kernel_for(lib, 32, 56, 56, 128, 128, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+8"      # four tiles: the compute waves store
     assert kernel_for(lib, 32, 7, 7, 2048, 512, 1, 1, 1, 0, 1, bf16).startswith("d64x64")     # 1568 output pixels
     for args in [(3, 17, 19, 8, 8, 1, 1, 1, 0, 1, 2), (5, 9, 33, 48, 24, 5, 3, 2, 2, 1, 3), (1, 1, 1, 8, 1, 1, 1, 1, 0, 1, 4),
                  (2, 40, 40, 96, 200, 3, 3, 1, 4, 4, bf16), (7, 12, 12, 64, 64, 3, 3, 1, 1, 1, bf16)]:
