@@ -34,9 +34,10 @@ int iconv_fwd_ex(const void *x_nhwc, const void *w_krsc, void *y_npqk,
                  int stride, int pad, int dilation, int dtype,
                  int variant, int max_workgroups, void *stream);
 
-/* The kernel table of the MFMA paths (block-level channel-first im2col, paper section 5, in its
- * per-tap, patch-reuse and resident-filter forms).  iconv_variant_name returns "auto" outside
- * 0 .. iconv_num_variants() - 1. */
+/* The kernel table: the MFMA paths (block-level channel-first im2col, paper section 5, in its
+ * per-tap, patch-reuse, resident-filter and pixel-resident forms) for channel counts that are
+ * multiples of eight, then the forms of the merged-tap kernel for four-channel layers (paper
+ * section 4.3).  iconv_variant_name returns "auto" outside 0 .. iconv_num_variants() - 1. */
 int iconv_num_variants(void);
 const char *iconv_variant_name(int variant);
 

@@ -89,12 +89,14 @@ int status_of(hipError_t e) { return e == hipSuccess ? ICONV_OK : ICONV_ERR_LAUN
 void drop_stale_error() { (void)hipGetLastError(); }
 
 // Runs the convolution with the fastest kernel that accepts the shape (variant < 0), or with the
-// kernel-table entry `variant` where that entry can run it.
+// kernel-table entry `variant` where that entry can run it.  The table: the MFMA kernels for channel counts
+// that are multiples of eight, then the forms of the merged-tap kernel for four-channel layers.
 int run_conv(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int variant, hipStream_t st) {
     drop_stale_error();
     if (in_t != IN_F32 && (s.C % 8) == 0)
         return status_of(launch_mfma(x, w, y, s, in_t, out_t, variant, st));
-    if (in_t != IN_F32 && stem_supported(s)) return status_of(launch_stem(x, w, y, s, in_t, out_t, st));
+    if (in_t != IN_F32 && stem_supported(s))
+        return status_of(launch_stem(x, w, y, s, in_t, out_t, variant - mfma_num_variants(), st));
     return status_of(launch_direct(x, w, y, s, in_t, out_t, st));
 }
 
@@ -184,7 +186,7 @@ int iconv_fwd_ex(const void* x, const void* w, void* y, int N, int H, int W, int
     if (rc != ICONV_OK) return rc;
     int in_t, out_t;
     if (!dtype_types(dtype, &in_t, &out_t)) return ICONV_ERR_UNSUPPORTED;
-    if (variant < -1 || variant >= mfma_num_variants() || max_workgroups < 0) return ICONV_ERR_UNSUPPORTED;
+    if (variant < -1 || variant >= iconv_num_variants() || max_workgroups < 0) return ICONV_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return ICONV_ERR_ALIGN;
     const int saved = tl_max_workgroups;
     tl_max_workgroups = max_workgroups;
@@ -308,23 +310,25 @@ const char* iconv_kernel_for(int N, int H, int W, int C, int K, int R, int S, in
     if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK) return nullptr;
     // same order as run_conv
     if (in_t != IN_F32 && (s.C % 8) == 0) return mfma_variant_name(mfma_default_variant(s));
-    if (in_t != IN_F32 && stem_supported(s)) return "stem";
+    if (in_t != IN_F32 && stem_supported(s)) return stem_variant_name(stem_choose(s));
     return "direct";
 }
 
-int iconv_num_variants(void) { return mfma_num_variants(); }
+int iconv_num_variants(void) { return mfma_num_variants() + stem_num_variants(); }
 
 int iconv_variant_accepts(int variant, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int dilation,
                           int dtype) {
     int in_t, out_t;
     ConvShape s;
     if (!dtype_types(dtype, &in_t, &out_t) || in_t == IN_F32) return 0;
-    if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK || (s.C % 8) != 0) return 0;
-    return mfma_variant_accepts(s, variant) ? 1 : 0;
+    if (make_shape(N, H, W, C, K, R, S, stride, pad, dilation, &s) != ICONV_OK) return 0;
+    if (variant >= mfma_num_variants()) return (s.C % 8) != 0 && stem_variant_supported(s, variant - mfma_num_variants()) ? 1 : 0;
+    return (s.C % 8) == 0 && mfma_variant_accepts(s, variant) ? 1 : 0;
 }
 
 const char* iconv_variant_name(int variant) {
-    if (variant < 0 || variant >= mfma_num_variants()) return "auto";
+    if (variant < 0 || variant >= iconv_num_variants()) return "auto";
+    if (variant >= mfma_num_variants()) return stem_variant_name(variant - mfma_num_variants());
     return mfma_variant_name(variant);
 }
 

@@ -97,8 +97,14 @@ const char* pointwise_variant_name(int v);
 hipError_t launch_pointwise(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t stream);
 
 // Merged-tap kernel for C == 4 first layers (stride 2, dilation 1, even W, S + (pad & 1) <= 8).
+// Two forms (0: four waves per workgroup that load, multiply and store; 1: eight compute and four store waves);
+// v outside the table, or a form the layer does not fit, means the form stem_choose names.
 bool stem_supported(const ConvShape& s);
-hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t,
+int stem_num_variants();
+const char* stem_variant_name(int v);
+bool stem_variant_supported(const ConvShape& s, int v);
+int stem_choose(const ConvShape& s);
+hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v,
                        hipStream_t stream);
 
 // Channel-last comparison kernel: NCHW input, KCRS filters, lowered columns ordered channel, tap row, tap column.

@@ -14,7 +14,9 @@
 // buffers after the current block's stores; the only synchronisation is one barrier per block.
 // The layer is bound by the write of y, which goes through a wave-private LDS staging area so that
 // every store instruction covers whole cache lines.  Two workgroups of four waves share a compute
-// unit (two waves per SIMD), which leaves each wave 256 vector registers.
+// unit (two waves per SIMD), which leaves each wave 256 vector registers.  A second form (stem_sw_kernel
+// below) gives the stores to waves of their own and is the one chosen once a compute unit has three or more
+// blocks to work through.
 #include <atomic>
 
 #include "iconv_common.h"
@@ -348,6 +350,271 @@ stem_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y
     }
 }
 
+// ---- the same kernel with STORE WAVES: eight compute waves (one 32-pixel fragment each, 256 pixels per block)
+// and four store waves in one workgroup per compute unit.  A wave that stores is held until the memory system
+// has taken its data, and this layer is bound by the write of y: here the compute waves deposit their fragments
+// in a 64 KiB staging area (fragment f, filter half ni at (2f + ni) * 4 KiB, layout stage_off) and go on with
+// the next block, while the store waves, which took the area into registers at the start of the tick, write the
+// previous block out.  Two barriers per block: S (the block's deposits are complete, the next patch is parked)
+// and M (the store waves hold the previous block in registers, the area may be overwritten).
+constexpr int kSwCompute = 8, kSwStore = 4, kSwWaves = kSwCompute + kSwStore;
+constexpr int kSwPatchItems = 2;                 // 16-byte patch pieces per compute lane at most (patch <= 16 KiB)
+constexpr int kSwStageBytes = kSwCompute * 2 * 4096;
+
+template <typename T, typename TO>
+__global__ void __launch_bounds__(kSwWaves * 64)
+stem_sw_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const StemGeom g) {
+    typedef typename Elem<T>::frag frag_t;
+    // [weights][patch 0][patch 1][output staging: 8 fragments x 2 filter halves x 4 KiB]
+    extern __shared__ u32x4 lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int TW = 1 << g.TW_LOG2;
+    constexpr int CT = kSwCompute * 64;         // compute threads: they load and park the patches
+
+    const int wg = xcd_remap(blockIdx.x, gridDim.x);
+    const int t_begin = wg * g.tiles_base + min(wg, g.tiles_rem);
+    const int t_end = t_begin + g.tiles_base + (wg < g.tiles_rem ? 1 : 0);
+    const int k0 = stem_decode(t_begin, g).k0;
+    const bool computes = wave < kSwCompute;
+
+    // ---- patch loads (compute waves): piece i of the lane is pixel pair (i * 512 + tid)
+    const uint32_t x_bytes = (uint32_t)s.N * s.H * s.W * 8u;
+    const rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), 0, x_bytes, kRsrcFlags);
+    const int npairs = g.PH * g.PPAIRS;
+    int p_h[kSwPatchItems], p_w[kSwPatchItems];
+#pragma unroll
+    for (int i = 0; i < kSwPatchItems; ++i) {
+        const int pi = i * CT + tid;
+        const int ph = (int)(((float)pi + 0.5f) * g.inv_ppairs);
+        const bool used = computes && pi < npairs && pi - ph * g.PPAIRS < g.PPAIRS_USED;
+        p_h[i] = used ? ph : 0;
+        p_w[i] = used ? 2 * (pi - ph * g.PPAIRS) : -(1 << 30);
+    }
+    auto load_patch = [&](int tile, u32x4 (&regs)[kSwPatchItems]) {
+        const StemTile tc = stem_decode(tile, g);
+        const int h_org = tc.p0 * s.stride - s.pad;
+        const int w_org = tc.q0 * s.stride - s.pad - g.shift;
+        const int base = (tc.n * s.H + h_org) * s.W + w_org;
+#pragma unroll
+        for (int i = 0; i < kSwPatchItems; ++i) {
+            if (i * CT < npairs) {                                  // uniform
+                const int h = h_org + p_h[i], ww = w_org + p_w[i];
+                const bool ok = ((unsigned)h < (unsigned)s.H) & ((unsigned)ww < (unsigned)s.W);
+                const uint32_t off = (uint32_t)(base + p_h[i] * s.W + p_w[i]) * 8u;
+                regs[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, ok ? off : x_bytes, 0, 0));
+            }
+        }
+    };
+    auto park_patch = [&](int buf, const u32x4 (&regs)[kSwPatchItems]) {
+        u32x4* dst = lds + ((g.b_bytes + buf * g.patch_bytes) >> 4) + tid;
+#pragma unroll
+        for (int i = 0; i < kSwPatchItems; ++i)
+            if (i * CT < npairs && i * CT + tid < (g.patch_bytes >> 4)) dst[i * CT] = regs[i];
+    };
+    u32x4 pregs[kSwPatchItems];
+    if (computes) load_patch(t_begin, pregs);
+
+    // ---- weights, once, by all waves (the layout of the kernel above)
+    {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        uint2* b8 = reinterpret_cast<uint2*>(lds);
+        constexpr int nthreads = kSwWaves * 64;
+        const int npad = 8 - s.S;
+        const float inv_npad = npad > 0 ? 1.0f / (float)npad : 0.f;
+        for (int it = tid; it < kStemBN * s.R * npad; it += nthreads) {
+            const int k = it & (kStemBN - 1);
+            const int rj = it >> 6;
+            const int r = (int)(((float)rj + 0.5f) * inv_npad), jj = rj - r * npad;
+            const int j = jj < g.shift ? jj : jj + s.S;
+            const int rc = r * 4 + (j >> 1);
+            b8[((rc * kStemBN + (k ^ (rc & 15))) << 1) + (j & 1)] = uint2{0u, 0u};
+        }
+        const int RS = s.R * s.S;
+        const int items = kStemBN * RS;
+        const float inv_rs = 1.0f / (float)RS, inv_s = 1.0f / (float)s.S;
+        const uint32_t w_bytes = (uint32_t)s.K * RS * 8u;
+        const rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(w), 0, w_bytes, kRsrcFlags);
+        const uint32_t w_base = (uint32_t)k0 * RS * 8u;
+        for (int base = tid; base < items; base += nthreads * 8) {
+            u32x2 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int it = base + u * nthreads;
+                v[u] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(
+                                                    w_rsrc, it < items ? w_base + (uint32_t)it * 8u : w_bytes, 0, 0));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int it = base + u * nthreads;
+                const int k = (int)(((float)it + 0.5f) * inv_rs);
+                const int rs = it - k * RS;
+                const int r = (int)(((float)rs + 0.5f) * inv_s), j = rs - r * s.S + g.shift;
+                const int rc = r * 4 + (j >> 1);
+                if (it < items) b8[((rc * kStemBN + (k ^ (rc & 15))) << 1) + (j & 1)] = uint2{v[u].x, v[u].y};
+            }
+        }
+    }
+
+    const int npx = g.TH * TW;
+    constexpr int BM = kSwCompute * 32;
+    char* stage = reinterpret_cast<char*>(lds) + g.b_bytes + 2 * g.patch_bytes;
+    const int c8 = lane & 7, l3 = lane >> 3;
+    const size_t y_elems = (size_t)s.M * s.K;
+    const int nblocks = t_end - t_begin;
+
+    if (!computes) {
+        // =========================== store waves ============================================
+        // store wave sw carries fragments 2 sw and 2 sw + 1 (64 pixels), both filter halves
+        const int sw = wave - kSwCompute;
+        const uint32_t sr = stage_off(l3, c8);   // read-back: piece l%8 of pixel l/8 (+ 8j: 1024 bytes further on)
+        const uint32_t y_lane = (uint32_t)(l3 * s.K + 4 * c8) * (uint32_t)sizeof(TO);
+        bool k_ok[2];
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) k_ok[ni] = k0 + ni * 32 + 4 * c8 + 3 < s.K;
+        __syncthreads();                        // weights and patch 0 are in LDS
+        for (int it = 0; it <= nblocks; ++it) {
+            u32x4 out[2][2][4];
+            if (it > 0) {
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            out[f][ni][j] = *reinterpret_cast<const u32x4*>(stage + ((2 * sw + f) * 2 + ni) * 4096 + sr + j * 1024);
+            }
+            if (it < nblocks) __syncthreads();  // M: the area may be overwritten
+            if (it > 0) {
+                const StemTile tc = stem_decode(t_begin + it - 1, g);
+                const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K + k0;
+                const size_t rem = (y_elems - org) * sizeof(TO);
+                const rsrc_t y_rsrc = __builtin_amdgcn_make_buffer_rsrc(y + org, 0, rem > 0xffffffffull ? 0xffffffffu : (uint32_t)rem,
+                                                                       kRsrcFlags);
+                const bool edge = npx < BM || tc.p0 + g.TH > s.P || tc.q0 + TW > s.Q;    // uniform
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            bool ok = k_ok[ni];
+                            const int t0 = (2 * sw + f) * 32 + 8 * j;      // uniform
+                            if (edge) {
+                                const int t = t0 + l3;
+                                ok = ok && t < npx && tc.p0 + (t >> g.TW_LOG2) < s.P && tc.q0 + (t & (TW - 1)) < s.Q;
+                            }
+                            const uint32_t y_uni = (uint32_t)(((t0 >> g.TW_LOG2) * s.Q + (t0 & (TW - 1))) * s.K + ni * 32) * (uint32_t)sizeof(TO);
+                            if (ok) store_piece<TO>(out[f][ni][j], y_rsrc, y_lane + y_uni);
+                        }
+            }
+            if (it < nblocks) __syncthreads();  // S: the next block's deposits are complete
+        }
+        return;
+    }
+
+    // =========================== compute waves ==============================================
+    const int frow = lane & 31, fk = lane >> 5;
+    const char* lds_b = reinterpret_cast<const char*>(lds);
+    uint32_t a_off;                               // byte offset in the patch of the lane's run at filter row 0
+    {
+        const int t = wave * 32 + frow;
+        const int th = t >> g.TW_LOG2, tw = t & (TW - 1);
+        a_off = (uint32_t)(t < npx ? th * s.stride * g.PPAIRS + tw * (s.stride >> 1) + fk : fk) * 16u;
+    }
+    const uint32_t b_off = (uint32_t)(fk * kStemBN) * 16u;
+    const uint32_t b_lane = (uint32_t)(frow ^ fk) * 16u;
+    const uint32_t row_bytes = (uint32_t)g.PPAIRS * 16u;
+    bool zero_lo[2], zero_hi[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int j = 4 * kk + 2 * fk;
+        zero_lo[kk] = j < g.shift || j >= s.S + g.shift;
+        zero_hi[kk] = (j + 1) < g.shift || (j + 1) >= s.S + g.shift;
+    }
+    const bool mask_kk0 = g.shift != 0 || s.S + g.shift < 4;
+    const bool mask_kk1 = s.S + g.shift < 8;
+    char* stg = stage + wave * 2 * 4096;
+    uint32_t sw_off[4];                           // deposit offset per filter quad
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) sw_off[gq] = stage_off(frow, 2 * gq + fk);
+
+    park_patch(0, pregs);
+    // The patch of block b + 2 is requested in tick b and parked at the end of tick b + 1: a whole tick for the
+    // loads, which queue behind the store waves' stores.  Two register sets that swap roles every tick.
+    u32x4 pregs2[kSwPatchItems];
+    if (t_begin + 1 < t_end) load_patch(t_begin + 1, pregs);
+    __syncthreads();                            // weights and patch 0 are in LDS
+    auto tick = [&](int tile, u32x4 (&pcur)[kSwPatchItems], u32x4 (&pnxt)[kSwPatchItems]) __attribute__((always_inline)) {
+        const char* pa = lds_b + g.b_bytes + ((tile - t_begin) & 1) * g.patch_bytes;
+        const char* pb = lds_b + b_off;
+        floatx16 acc[2];
+        frag_t a0, b0[2], a1, b1[2];
+
+        auto fetch = [&](int r, int kk, frag_t& af, frag_t (&bf)[2]) {
+            af = *reinterpret_cast<const frag_t*>(pa + a_off + (uint32_t)r * row_bytes + kk * 32);
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                bf[ni] = *reinterpret_cast<const frag_t*>(pb + (b_lane ^ (uint32_t)(((4 * r + 2 * kk) & 15) << 4)) + r * 4096 +
+                                                          kk * 2048 + ni * 512);
+        };
+        auto mma = [&](frag_t& af, frag_t (&bf)[2], int kk, bool first) {
+            if (kk == 0 ? mask_kk0 : mask_kk1) {
+                u32x4 v = __builtin_bit_cast(u32x4, af);
+                if (zero_lo[kk]) { v.x = 0u; v.y = 0u; }
+                if (zero_hi[kk]) { v.z = 0u; v.w = 0u; }
+                af = __builtin_bit_cast(frag_t, v);
+            }
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                if (first) {
+                    floatx16 z;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                    acc[ni] = Elem<T>::mfma32(bf[ni], af, z);
+                } else {
+                    acc[ni] = Elem<T>::mfma32(bf[ni], af, acc[ni]);
+                }
+            }
+        };
+        const int r_last = s.R - 1;
+        fetch(0, 0, a0, b0);
+        fetch(0, 1, a1, b1);
+        mma(a0, b0, 0, true);
+        fetch(min(1, r_last), 0, a0, b0);
+        mma(a1, b1, 1, false);
+        // M after the first filter row: by now the store waves hold the previous block in registers, so neither
+        // side waits long
+        __syncthreads();
+        if (tile + 2 < t_end) load_patch(tile + 2, pnxt);
+        for (int r = 1; r < s.R; ++r) {
+            fetch(r, 1, a1, b1);
+            mma(a0, b0, 0, false);
+            fetch(min(r + 1, r_last), 0, a0, b0);
+            mma(a1, b1, 1, false);
+        }
+        // deposit: lane l holds block pixel 32*wave + l%32 and, in accumulator element v, filter
+        // 8*(v/4) + 4*(l/32) + v%4 of the 32-wide half
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                u32x4 v;
+                v.x = __float_as_uint(acc[ni][4 * gq]);     v.y = __float_as_uint(acc[ni][4 * gq + 1]);
+                v.z = __float_as_uint(acc[ni][4 * gq + 2]); v.w = __float_as_uint(acc[ni][4 * gq + 3]);
+                *reinterpret_cast<u32x4*>(stg + ni * 4096 + sw_off[gq]) = v;
+            }
+        if (tile + 1 < t_end) park_patch((tile + 1 - t_begin) & 1, pcur);
+        __syncthreads();                        // S: deposits complete, next patch in LDS
+    };
+    for (int tile = t_begin; tile < t_end; tile += 2) {
+        tick(tile, pregs, pregs2);
+        if (tile + 1 < t_end) tick(tile + 1, pregs2, pregs);
+    }
+}
+
 constexpr int kStemMI = 2;                       // 4 waves x 2 fragments x 32 = 256 output pixels per block
 constexpr int kStemLdsLimit = 80 * 1024;     // two workgroups per compute unit
 constexpr int kStemStageBytes = kStemWaves * 4096;
@@ -381,6 +648,33 @@ bool plan_stem(const ConvShape& s, StemGeom* g) {
     if (total > 0x7fffffffL) return false;
     g->total_tiles = (int)total;
     return true;
+}
+
+constexpr int kSwLdsLimit = 160 * 1024;      // one workgroup per compute unit
+
+// The form with store waves needs whole 16-byte pieces of y rows, one filter tile, and its staging area in LDS.
+bool stem_sw_fits(const ConvShape& s, const StemGeom& g) {
+    return g.tiles_n == 1 && (s.K & 3) == 0 && g.b_bytes + 2 * g.patch_bytes + kSwStageBytes <= kSwLdsLimit;
+}
+
+template <typename T, typename TO>
+hipError_t launch_stem_sw_t(const void* x, const void* w, void* y, const ConvShape& s, StemGeom g, hipStream_t st) {
+    const int lds_bytes = g.b_bytes + 2 * g.patch_bytes + kSwStageBytes;
+    auto kern = stem_sw_kernel<T, TO>;
+    static std::atomic<bool> raised{false};
+    if (!raised.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kSwLdsLimit);
+        if (e != hipSuccess) return e;
+        raised.store(true, std::memory_order_release);
+    }
+    // one workgroup per compute unit, each with an equal range of blocks
+    const int cap = call_max_workgroups();
+    const long slots = cap > 0 ? cap : (long)device_cus();
+    const int nwg = (int)(g.total_tiles < slots ? g.total_tiles : slots);
+    g.tiles_base = g.total_tiles / nwg;
+    g.tiles_rem = g.total_tiles % nwg;
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kSwWaves * 64), lds_bytes, st, (const T*)x, (const T*)w, (TO*)y, s, g);
+    return hipGetLastError();
 }
 
 template <typename T, typename TO>
@@ -421,9 +715,35 @@ bool stem_supported(const ConvShape& s) {
     return plan_stem(s, &g);
 }
 
-hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, hipStream_t st) {
+// Two forms: 0 = four waves that load, multiply and store, two workgroups per compute unit; 1 = eight compute
+// and four store waves, one workgroup per compute unit.
+int stem_num_variants() { return 2; }
+const char* stem_variant_name(int v) { return v == 1 ? "stem_8+4" : "stem"; }
+bool stem_variant_supported(const ConvShape& s, int v) {
+    StemGeom g;
+    if (!plan_stem(s, &g)) return false;
+    return v == 0 || (v == 1 && stem_sw_fits(s, g));
+}
+// The form with store waves is the faster one (-6 % at 3 blocks per compute unit, -7 % at 6 and 12) once every
+// compute unit has a few blocks to pipeline; with 1.5 blocks per compute unit it is 4 % slower.
+int stem_choose(const ConvShape& s) {
+    StemGeom g;
+    if (!plan_stem(s, &g)) return -1;
+    return stem_sw_fits(s, g) && g.total_tiles >= 3L * device_cus() ? 1 : 0;
+}
+
+hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t st) {
     StemGeom g;
     if (!plan_stem(s, &g)) return hipErrorInvalidConfiguration;
+    if (v < 0 || v >= stem_num_variants() || !stem_variant_supported(s, v)) v = stem_choose(s);
+    if (v == 1) {
+        if (in_t == IN_BF16) {
+            if (out_t == OUT_F32) return launch_stem_sw_t<bf16_t, float>(x, w, y, s, g, st);
+            return launch_stem_sw_t<bf16_t, bf16_t>(x, w, y, s, g, st);
+        }
+        if (out_t == OUT_F32) return launch_stem_sw_t<f16_t, float>(x, w, y, s, g, st);
+        return launch_stem_sw_t<f16_t, f16_t>(x, w, y, s, g, st);
+    }
     if (in_t == IN_BF16) {
         if (out_t == OUT_F32) return launch_stem_t<bf16_t, float>(x, w, y, s, g, st);
         return launch_stem_t<bf16_t, bf16_t>(x, w, y, s, g, st);

@@ -130,7 +130,7 @@ def kernel_for(lib, *args):
 
 def test_kernel_choice_follows_the_layer_class(lib):
     """iconv_kernel_for (host logic; 256 compute units are assumed without a device): each class of layer gets the
-    kernel family built for it, every answer is a kernel-table name or "stem"/"direct", invalid arguments give NULL."""
+    kernel family built for it, every answer is a kernel-table name or "direct", invalid arguments give NULL."""
     lib.iconv_variant_name.restype = ctypes.c_char_p
     table = {lib.iconv_variant_name(i).decode() for i in range(lib.iconv_num_variants())}
     bf16 = 1
@@ -143,7 +143,9 @@ def test_kernel_choice_follows_the_layer_class(lib):
     assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16) == "a128x32_2x4+4+4"        # 1x1: pixels resident, store waves
     assert kernel_for(lib, 8, 64, 64, 256, 256, 3, 3, 1, 2, 2, bf16).startswith("p256x128")
     assert kernel_for(lib, 64, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16).startswith("p64x128_c128")
-    assert kernel_for(lib, 64, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem"
+    assert kernel_for(lib, 64, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem_8+4"           # 12 blocks per compute unit: store waves
+    assert kernel_for(lib, 8, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem"                # 1.5 blocks per compute unit
+    assert kernel_for(lib, 64, 224, 224, 4, 62, 7, 7, 2, 3, 1, bf16) == "stem"               # K % 4 != 0
     assert kernel_for(lib, 1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 0) == "direct"            # fp32
     assert kernel_for(lib, 2, 8, 8, 20, 16, 3, 3, 1, 1, 1, bf16) == "direct"         # C % 8 != 0
     # tile size follows the tile count: the same layers at other batch sizes
@@ -165,7 +167,7 @@ def test_kernel_choice_follows_the_layer_class(lib):
     for args in [(3, 17, 19, 8, 8, 1, 1, 1, 0, 1, 2), (5, 9, 33, 48, 24, 5, 3, 2, 2, 1, 3), (1, 1, 1, 8, 1, 1, 1, 1, 0, 1, 4),
                  (2, 40, 40, 96, 200, 3, 3, 1, 4, 4, bf16), (7, 12, 12, 64, 64, 3, 3, 1, 1, 1, bf16)]:
         name = kernel_for(lib, *args)
-        assert name in table or name in ("stem", "direct"), (args, name)
+        assert name in table or name == "direct", (args, name)
     # what iconv_fwd rejects
     assert kernel_for(lib, 0, 8, 8, 16, 16, 3, 3, 1, 1, 1, bf16) is None             # shape
     assert kernel_for(lib, 1, 2, 2, 16, 16, 3, 3, 1, 0, 1, bf16) is None             # empty output

@@ -186,7 +186,7 @@ def test_resident_filter_kernels(B):
               workloads.small_layer("r_k", 5, 56, 56, 64, 44, 3, 3, 1, 1, 1, seed_id=850),     # five blocks per image row group, K = 44
               workloads.small_layer("r_l", 2, 50, 56, 32, 64, 5, 3, 1, 2, 1, dtype="f16", seed_id=851)]   # five filter rows, ragged last block
     names = variant_names(B)
-    res = [v for v, nm in enumerate(names) if nm[0] in "rts"]
+    res = [v for v, nm in enumerate(names) if nm[0] in "rts" and nm[1].isdigit()]
     assert len(res) == 6
     ran = 0
     for cap in (0, 1, 3):
@@ -238,10 +238,21 @@ def test_merged_tap_workgroups_walking_several_blocks(B):
               workloads.small_layer("m_b", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1, seed_id=831),    # 32-wide blocks, even pad
               workloads.small_layer("m_c", 5, 24, 40, 4, 24, 3, 3, 2, 1, 1, dtype="f16", seed_id=832),
               workloads.small_layer("m_d", 2, 30, 36, 4, 64, 7, 7, 2, 3, 1, seed_id=833)]
+    shapes.append(workloads.small_layer("m_e", 2, 64, 64, 4, 62, 7, 7, 2, 3, 1, seed_id=834))    # K % 4 != 0: only the first form
+    names = variant_names(B)
+    forms = [i for i, nm in enumerate(names) if nm.startswith("stem")]
+    assert [names[i] for i in forms] == ["stem", "stem_8+4"]        # four waves that do everything / eight compute + four store waves
+    ran = 0
     for cap in (0, 1, 2, 3):
         for L in shapes:
-            print("cap", cap, L.name, flush=True)
-            check(B, L, cap=cap)
+            for v in forms:
+                if not B.iconv_variant_accepts(v, *L.shape_args(), code_of(L)):
+                    assert v == forms[1] and L.K % 4 != 0, (names[v], L.name)
+                    continue
+                print("cap", cap, names[v], L.name, flush=True)
+                check(B, L, variant=v, cap=cap)
+                ran += 1
+    assert ran == 4 * (2 * 4 + 1)
 
 
 def test_staged_output_repeated_runs(B):
@@ -320,8 +331,10 @@ OUT16_CASES = [
     ("patch_pf_small_tiles", "p64x128_c64_w32x64_s4_4+4_pf", 0, ("o_p19", 5, 7, 7, 136, 160, 3, 3, 1, 1, 1)),
     ("patch_c128", "p64x128_c128", 2, ("o_p20", 6, 7, 7, 256, 128, 3, 3, 1, 1, 1)),
     ("patch_k_odd", "p64x64", 0, ("o_p7", 2, 14, 15, 40, 37, 3, 3, 1, 1, 1)),
-    ("stem", "", 0, ("o_stem", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1)),
-    ("stem_walk_k40", "", 2, ("o_stem2", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1)),
+    ("stem", "stem", 0, ("o_stem", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1)),
+    ("stem_walk_k40", "stem", 2, ("o_stem2", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1)),
+    ("stem_store_waves", "stem_8+4", 0, ("o_stem3", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1)),
+    ("stem_store_waves_walk_k40", "stem_8+4", 2, ("o_stem4", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1)),
     ("direct_c3", "", 0, ("o_d3", 2, 9, 10, 3, 5, 3, 3, 1, 1, 1)),
 ]
 
@@ -337,8 +350,8 @@ def test_sixteen_bit_output_through_every_epilogue(B, case, dtype):
         assert hits, f"no kernel-table entry starts with {forced}"
         v = hits[0]
         assert B.iconv_variant_accepts(v, *L.shape_args(), code_of(L, out16=True)), f"{forced} does not take {dims}"
-    elif L.C % 8 == 0:
-        pytest.fail("cases without a forced entry are meant for the stem and direct kernels")
+    elif L.C % 8 == 0 or L.C == 4:
+        pytest.fail("cases without a forced entry are meant for the direct kernel")
     check_sixteen_bit(B, L, variant=v, cap=cap)
 
 
