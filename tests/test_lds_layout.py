@@ -174,6 +174,26 @@ def test_output_staging(lib):
     assert write_turns([16 * l for l in range(64)]) == 8
 
 
+def test_store_wave_staging(lib):
+    """The forms with store waves share one staging area per workgroup, laid out by the same function over more
+    pixels.  1x1 kernel (csrc/iconv_pointwise.hip): compute wave wq deposits piece 2*gq + l/32 of pixel 32*wq + l%32
+    with all 64 lanes; store wave sw reads piece l%8 of pixel 8*(2*i + sw/2) + l/8, i = 0..7.  Merged-tap kernel
+    (csrc/iconv_stem.hip): a fragment's 32 pixels x 8 pieces sit in a 4 KiB area of their own, deposit as above,
+    read-back of pixels l/8 + 8j.  No bank conflicts, and the 128 pixels x 8 pieces of a tile do not overlap."""
+    off = lib.iconv_lds_stage_offset
+    assert len({off(i, c) for i in range(128) for c in range(8)}) == 1024
+    assert max(off(i, c) for i in range(128) for c in range(8)) == 128 * 128 - 16
+    for wq in range(4):
+        for gq in range(4):
+            assert write_turns([off(32 * wq + (l & 31), 2 * gq + (l >> 5)) for l in range(64)]) == 8
+    for g0 in range(2):
+        for i in range(8):
+            assert turns([off(8 * (2 * i + g0) + (l >> 3), l & 7) for l in range(64)]) == 4
+    for j in range(4):
+        assert turns([off(l >> 3, l & 7) + 1024 * j for l in range(64)]) == 4
+        assert {off(l >> 3, l & 7) + 1024 * j for l in range(64)} == {off(8 * j + (l >> 3), l & 7) for l in range(64)}
+
+
 def test_merged_tap_kernel_patch_reads():
     """csrc/iconv_stem.hip: the patch holds 16-byte pixel pairs, row pitch PPAIRS pairs; lane l of fragment f reads
     the pair at (th * stride * PPAIRS + tw * stride / 2 + l/32) of block pixel t = 32 f + l%32 (th = t / TW,
