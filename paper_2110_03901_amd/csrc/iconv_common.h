@@ -67,7 +67,7 @@ hipError_t launch_mfma(const void* x, const void* w, void* y, const ConvShape& s
 
 // Patch-reuse kernels (channel chunk outer, tap inner; input patch resident in LDS).  Table order:
 enum PatchVariant { kP128x64, kP256x128, kP256x64, kP64x64, kP64x128, kP128x64Staged, kP256x128Pf, kP64x128Pf, kP64x128C128,
-                    kNumPatch };
+                    kP64x128C128K2, kNumPatch };
 int patch_num_variants();
 const char* patch_variant_name(int v);
 bool patch_supported(const ConvShape& s, int v);

@@ -374,7 +374,11 @@ int choose_variant(const ConvShape& s) {
         else if (tiles_256x128 >= 190)                // p256x128; with many channel chunks per tap, operands prefetched
             v = s.C >= 256 ? kP256x128Pf : kP256x128; // one group of K slices ahead
         else if (tiles_256x64 >= 190) v = kP256x64;   // p256x64 when that still gives most compute units a tile
-        else if (s.C % 128 == 0) v = kP64x128C128;    // p64x128 (many small tiles), 128-channel chunks: half the steps
+        else if (s.C % 128 == 0) {                    // p64x128 (many small tiles), 128-channel chunks: half the steps;
+            v = kP64x128C128;                         // with one round of workgroups, two compute waves per tile
+            const long tiles_64x128 = (long)((s.M + 63) / 64) * ((s.K + 127) / 128);   // position on half the K slices each
+            if (tiles_64x128 <= device_cus() && patch_supported(s, kP64x128C128K2)) v = kP64x128C128K2;
+        }
         else v = kP64x128Pf;                          // p64x128, prefetching
         if (patch_supported(s, v)) return P0 + v;
         if (v != kP64x128 && s.K > 64 && patch_supported(s, kP64x128)) return P0 + kP64x128;

@@ -114,10 +114,15 @@ template <int BN> __device__ __forceinline__ TileCoord decode_tile(int t, const 
 template <int V> struct IntTag { static constexpr int value = V; };
 
 template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
-          int PF>
-__global__ void __launch_bounds__((WAVES_M * WAVES_N + NLD + NSW) * 64)
+          int PF, int KS>
+__global__ void __launch_bounds__((WAVES_M * WAVES_N * KS + NLD + NSW) * 64)
 ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__ y, const ConvShape s, const PatchGeom g) {
-    constexpr int WAVES_C = WAVES_M * WAVES_N;  // compute waves
+    // KS == 2: two compute waves per tile position, each with the K slices of one half of every step (so that every
+    // SIMD has two waves issuing MFMAs while a wave still owns a 32 x 64 output); their partial sums meet in LDS
+    // after the last step.  Only for workgroups with one tile, whole 16-byte output pieces and no prefetch pipeline.
+    constexpr int WAVES_P = WAVES_M * WAVES_N;  // tile positions
+    constexpr int WAVES_C = WAVES_P * KS;       // compute waves
+    static_assert(KS == 1 || (KS == 2 && PF == 0 && SS == 0 && CB >= 64), "K split: two halves of the plain loop");
     constexpr int CPR = CB / 8;                 // 16-byte chunks per pixel (or filter row) and channel chunk
     constexpr int RPB = 64 / CPR;               // pixels (filter rows) one wave-wide load covers
     constexpr int PPW = 16 / CPR;               // pixels per 256-byte LDS window
@@ -187,6 +192,15 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         const int a_ph0 = a_pp0 / g.PW;
         const int a_pw0 = a_pp0 - a_ph0 * g.PW;
         int a_ph, a_pw, a_j;                    // running state within one phase
+        // The lane's pixel as (image of the tile, row within that image's patch) and as a byte offset into x, all
+        // advanced by additions: a load moves the pixel by dph rows and dpw columns (+ a row when the column wraps,
+        // + an image when the row leaves the image's patch, which the host allows at most once per load).
+        int a_gi = 0, a_phi = 0;
+        uint32_t a_off = 0;
+        // (modulo 2^32 throughout: an offset is only used when its pixel exists, and then it is below 2^31)
+        const uint32_t a_step0 = (uint32_t)(g.dph * s.W + g.dpw) * (uint32_t)s.C * 2u;
+        const uint32_t a_stepw = (uint32_t)(s.W - g.PW) * (uint32_t)s.C * 2u;
+        const uint32_t a_stepg = (uint32_t)(s.H - g.PH) * (uint32_t)s.W * (uint32_t)s.C * 2u;
         int a_n = 0, a_hb = 0, a_wb = 0, a_c0 = 0, a_buf = 0;   // phase being loaded: image, patch origin, chunk, buffer
         bool a_live = false;
         auto patch_begin = [&](int phase) {     // point the patch loader at phase `phase` (or switch it off)
@@ -199,22 +213,31 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 a_wb = tc.q0 * s.stride - s.pad;
                 a_c0 = (phase % chunks) * CB;
                 a_buf = phase & 1;
+                a_gi = g.G > 1 ? (int)(((float)a_ph + 0.5f) * g.inv_ph) : 0;
+                a_phi = a_ph - a_gi * g.PH;
+                a_off = (uint32_t)((((a_n + a_gi) * s.H + a_hb + a_phi) * s.W + a_wb + a_pw) * s.C + a_c0 + a_lc) * 2u;
             }
         };
         // one patch load (or a no-op load into the sink once the phase's patch is complete)
         auto patch_load = [&](bool allowed) {
-            const int gi = g.G > 1 ? (int)(((float)a_ph + 0.5f) * g.inv_ph) : 0;     // image of the tile this patch row belongs to
-            const int h = a_hb + a_ph - gi * g.PH, ww = a_wb + a_pw;
+            const int h = a_hb + a_phi, ww = a_wb + a_pw;
             const bool real = allowed && a_live && a_j < g.a_blocks;   // wave-uniform
-            const bool ok = real & (a_ph < g.G * g.PH) & (a_n + gi < s.N) & ((unsigned)h < (unsigned)s.H) &
+            const bool ok = real & (a_ph < g.G * g.PH) & (a_n + a_gi < s.N) & ((unsigned)h < (unsigned)s.H) &
                             ((unsigned)ww < (unsigned)s.W) & ((a_c0 + a_lc) < s.C);
-            const uint32_t off = (uint32_t)((((a_n + gi) * s.H + h) * s.W + ww) * s.C + a_c0 + a_lc) * 2u;
             const uint32_t dst = real ? lds_base + (uint32_t)a_buf * g.patch_bytes + (uint32_t)(lw + a_j * NLD) * 1024u : sink;
-            dma16(x_rsrc, ok ? off : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
+            dma16(x_rsrc, ok ? a_off : x_bytes, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
             a_pw += g.dpw;
             const int wrap = a_pw >= g.PW ? 1 : 0;
             a_pw -= wrap ? g.PW : 0;
             a_ph += g.dph + wrap;
+            a_phi += g.dph + wrap;
+            a_off += a_step0 + (wrap ? a_stepw : 0u);
+            if (g.G > 1) {                      // uniform
+                const int cross = a_phi >= g.PH ? 1 : 0;
+                a_phi -= cross ? g.PH : 0;
+                a_gi += cross;
+                a_off += cross ? a_stepg : 0u;
+            }
             ++a_j;
         };
 
@@ -361,7 +384,9 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
     }
 
     // =============================== compute waves ==============================================
-    const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+    const int kh = wave / WAVES_P;              // K half of this wave (0 when KS == 1)
+    const int wpos = wave - kh * WAVES_P;
+    const int wave_m = wpos / WAVES_N, wave_n = wpos % WAVES_N;
     const int frow = lane & 31, fk = lane >> 5;
     const int npx = g.G * g.TH * g.TW;
     int a_base[MI];                             // patch pixel of each A-fragment row at tap (0, 0)
@@ -396,6 +421,33 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         // barrier counts live waves only, so the ended loader waves do not take part.)
         if (SS == 0 && tile == t_end - 1 && vec_ok && (long long)g.G * g.TH * s.Q * s.K * (long long)sizeof(TO) < 0x7fffffffLL) {
             __syncthreads();
+            if constexpr (KS == 2) {
+                // partial sums of the upper K half: lane-linear 16-byte pieces behind the staging areas
+                u32x4* red = lds + ((WAVES_C * kFragStageBytes) >> 4) + wpos * (MI * NI * 4 * 64) + lane;
+                if (kh == 1) {
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                floatx4 v = {acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1], acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]};
+                                red[((mi * NI + ni) * 4 + q) * 64] = __builtin_bit_cast(u32x4, v);
+                            }
+                }
+                __syncthreads();
+                if (kh == 1) return;
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const floatx4 v = __builtin_bit_cast(floatx4, red[((mi * NI + ni) * 4 + q) * 64]);
+                            acc[mi][ni][4 * q] += v[0]; acc[mi][ni][4 * q + 1] += v[1];
+                            acc[mi][ni][4 * q + 2] += v[2]; acc[mi][ni][4 * q + 3] += v[3];
+                        }
+            }
             char* stg = reinterpret_cast<char*>(lds) + wave * kFragStageBytes;
             const size_t org = ((size_t)(tc.n * s.P + tc.p0) * s.Q + tc.q0) * s.K;
             const size_t rem = ((size_t)s.M * s.K - org) * sizeof(TO);
@@ -602,8 +654,10 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 // group's MFMAs into the pipe
                 constexpr int KG = KI >= 4 ? 2 : 1;     // groups per step
                 constexpr int KPG = KI / KG;            // K slices per group
+                static_assert(KS == 1 || KG == 2, "the K split takes one group each");
 #pragma unroll
                 for (int gk = 0; gk < KG; ++gk) {
+                    if (KS == 2 && gk != kh) continue;      // uniform: the other half is the other wave's
                     frag_t af[KPG][MI], bfr[KPG][NI];
 #pragma unroll
                     for (int k2 = 0; k2 < KPG; ++k2) {
@@ -656,10 +710,10 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 
 struct PatchCfg {
     const char* name;
-    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw, pf;
+    int cb, waves_m, waves_n, mi, ni, stb, la, nld, ss, nsw, pf, ks;
     int bm() const { return waves_m * mi * 32; }
     int bn() const { return waves_n * ni * 32; }
-    int waves() const { return waves_m * waves_n + nld + nsw; }   // compute + loader + store waves
+    int waves() const { return waves_m * waves_n * ks + nld + nsw; }   // compute + loader + store waves
     // LDS after the patches, the filter ring and the sinks: output staging for the store waves
     long tail_bytes() const { return ss > 0 ? (long)bm() * bn() * 4 : 0; }
 };
@@ -671,6 +725,8 @@ constexpr int kLdsLimit = 160 * 1024;
 bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
     const int BM = c.bm();
     if ((double)s.K * s.Kg * 4.0 >= 4294967296.0) return false;   // out-of-range filter offsets must not wrap (see filter_tile)
+    // the K split adds its partial sums in the staged epilogue of a workgroup's only tile: whole 16-byte pieces
+    if (c.ks == 2 && (s.K & 3) != 0) return false;
     if (c.ss > 0) {
         // the staged epilogue stores through a 32-bit buffer descriptor, needs K % 4 == 0 for whole
         // 16-byte pieces, and must get a tile out within the steps of the next one
@@ -727,6 +783,7 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
             const long patch_bytes = (long)a_blocks * c.nld * 1024;
             const long lds = 2 * patch_bytes + (long)c.stb * c.bn() * c.cb * 2 + c.nld * 1024 + c.tail_bytes();
             if (lds > kLdsLimit || (long)c.la * (RS - c.stb + 1) < a_blocks) continue;
+            if (per_pass / g->PW + 1 > g->PH) break;    // a patch load must not skip an image (the loader adds at most one)
             g->G = G;
             g->npix = (int)npix;
             g->a_blocks = a_blocks;
@@ -734,16 +791,18 @@ bool plan_geometry(const ConvShape& s, const PatchCfg& c, PatchGeom* g) {
             break;
         }
     }
+    // (the staged epilogue addresses a tile's outputs with 31 bits)
+    if (c.ks == 2 && (long long)g->G * g->TH * s.Q * s.K * 4LL >= 0x7fffffffLL) return false;
     return true;
 }
 
 template <typename T, typename TO, int CB, int WAVES_M, int WAVES_N, int MI, int NI, int STB, int LA, int NLD, int SS, int NSW,
-          int PF>
+          int PF, int KS>
 hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     PatchGeom g;
     if (!plan_geometry(s, c, &g)) return hipErrorInvalidConfiguration;
     const int lds_bytes = 2 * g.patch_bytes + STB * c.bn() * CB * 2 + NLD * 1024 + (int)c.tail_bytes();
-    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW, PF>;
+    auto kern = ipatch_kernel<T, TO, CB, WAVES_M, WAVES_N, MI, NI, STB, LA, NLD, SS, NSW, PF, KS>;
     static std::atomic<bool> raised{false};
     if (!raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
@@ -761,7 +820,10 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
     const long w_bytes = (long)s.K * s.Kg * 2, x_bytes = (long)s.N * s.H * s.W * s.C * 2;
     g.n_slow = (g.tiles_n > 1 && w_bytes >= (2L << 20) && w_bytes > x_bytes) ? 1 : 0;
     const int cap = call_max_workgroups();
-    if (cap > 0) {
+    if (KS == 2) {
+        g.tiles_per_wg = 1;                     // the partial sums meet in LDS the loaders no longer use
+        nwg = (int)total;
+    } else if (cap > 0) {
         split_tiles(total, cap, 1, &g.tiles_per_wg, &nwg);
     } else {
         split_tiles(total, device_cus(), occ, &g.tiles_per_wg, &nwg);
@@ -772,19 +834,21 @@ hipError_t launch_cfg(const PatchCfg& c, const void* x, const void* w, void* y, 
 
 //   name                                  CB  WM WN MI NI STB LA NLD SS NSW PF
 // (compute + loader [+ store] waves; SS > 0: output staged in LDS and drained by NSW store waves;
-//  PF: operands of the next group of K slices are read before the current group's MFMAs)
+//  PF: operands of the next group of K slices are read before the current group's MFMAs; KS = 2: two compute waves
+//  per tile position, one K half each: "4x2")
 #define ICONV_PATCH_VARIANTS(X)                                                              \
-    X(kP128x64, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 0)                \
-    X(kP256x128, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 0)              \
-    X(kP256x64, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 0)                \
-    X(kP64x64, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 0)                  \
-    X(kP64x128, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)                \
-    X(kP128x64Staged, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 0)        \
-    X(kP256x128Pf, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1)         \
-    X(kP64x128Pf, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1)           \
-    X(kP64x128C128, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0)
+    X(kP128x64, "p128x64_c64_w32x64_s3_4+4", 64, 4, 1, 1, 2, 3, 1, 4, 0, 0, 0, 1)                \
+    X(kP256x128, "p256x128_c64_w64x64_s3_8+4", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 0, 1)              \
+    X(kP256x64, "p256x64_c64_w32x64_s3_8+4", 64, 8, 1, 1, 2, 3, 2, 4, 0, 0, 0, 1)                \
+    X(kP64x64, "p64x64_c64_w32x32_s3_4+4", 64, 2, 2, 1, 1, 3, 1, 4, 0, 0, 0, 1)                  \
+    X(kP64x128, "p64x128_c64_w32x64_s3_4+4", 64, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0, 1)                \
+    X(kP128x64Staged, "p128x64_c64_w32x64_s3_4+4+2", 64, 4, 1, 1, 2, 3, 2, 4, 2, 2, 0, 1)        \
+    X(kP256x128Pf, "p256x128_c64_w64x64_s3_8+4_pf", 64, 4, 2, 2, 2, 3, 2, 4, 0, 0, 1, 1)         \
+    X(kP64x128Pf, "p64x128_c64_w32x64_s4_4+4_pf", 64, 2, 2, 1, 2, 4, 1, 4, 0, 0, 1, 1)           \
+    X(kP64x128C128, "p64x128_c128_w32x64_s3_4+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0, 1)      \
+    X(kP64x128C128K2, "p64x128_c128_w32x64_s3_4x2+4", 128, 2, 2, 1, 2, 3, 1, 4, 0, 0, 0, 2)
 
-#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf},
+#define X_CFG(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf, ks) {name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf, ks},
 const PatchCfg kPatchCfgs[] = {ICONV_PATCH_VARIANTS(X_CFG)};
 #undef X_CFG
 static_assert(sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]) == kNumPatch, "one configuration per kernel");
@@ -792,8 +856,8 @@ static_assert(sizeof(kPatchCfgs) / sizeof(kPatchCfgs[0]) == kNumPatch, "one conf
 template <typename T, typename TO>
 hipError_t launch_patch_t(int v, const void* x, const void* w, void* y, const ConvShape& s, hipStream_t st) {
     switch (v) {
-#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf) \
-    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf>(kPatchCfgs[i], x, w, y, s, st);
+#define X_CASE(i, name, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf, ks) \
+    case i: return launch_cfg<T, TO, cb, wm, wn, mi, ni, stb, la, nld, ss, nsw, pf, ks>(kPatchCfgs[i], x, w, y, s, st);
         ICONV_PATCH_VARIANTS(X_CASE)
 #undef X_CASE
         default: return hipErrorInvalidValue;

@@ -142,7 +142,8 @@ def test_kernel_choice_follows_the_layer_class(lib):
     assert kernel_for(lib, 32, 56, 56, 128, 128, 3, 3, 2, 1, 1, bf16).startswith("d128x128")
     assert kernel_for(lib, 32, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16) == "a128x32_2x4+4+4"        # 1x1: pixels resident, store waves
     assert kernel_for(lib, 8, 64, 64, 256, 256, 3, 3, 1, 2, 2, bf16).startswith("p256x128")
-    assert kernel_for(lib, 64, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16).startswith("p64x128_c128")
+    assert kernel_for(lib, 64, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16) == "p64x128_c128_w32x64_s3_4x2+4"   # one round: K split over two waves
+    assert kernel_for(lib, 96, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16) == "p64x128_c128_w32x64_s3_4+4"    # 384 tiles: more than one round
     assert kernel_for(lib, 64, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem_8+4"           # 12 blocks per compute unit: store waves
     assert kernel_for(lib, 8, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem"                # 1.5 blocks per compute unit
     assert kernel_for(lib, 64, 224, 224, 4, 62, 7, 7, 2, 3, 1, bf16) == "stem"               # K % 4 != 0

@@ -330,6 +330,7 @@ OUT16_CASES = [
     ("patch_pf", "p256x128_c64_w64x64_s3_8+4_pf", 1, ("o_p17", 2, 20, 22, 136, 200, 3, 3, 1, 1, 1)),
     ("patch_pf_small_tiles", "p64x128_c64_w32x64_s4_4+4_pf", 0, ("o_p19", 5, 7, 7, 136, 160, 3, 3, 1, 1, 1)),
     ("patch_c128", "p64x128_c128", 2, ("o_p20", 6, 7, 7, 256, 128, 3, 3, 1, 1, 1)),
+    ("patch_c128_k_split", "p64x128_c128_w32x64_s3_4x2", 0, ("o_p21", 6, 7, 7, 256, 136, 3, 3, 1, 1, 1)),
     ("patch_k_odd", "p64x64", 0, ("o_p7", 2, 14, 15, 40, 37, 3, 3, 1, 1, 1)),
     ("stem", "stem", 0, ("o_stem", 2, 64, 64, 4, 64, 7, 7, 2, 3, 1)),
     ("stem_walk_k40", "stem", 2, ("o_stem2", 2, 66, 128, 4, 40, 5, 5, 2, 2, 1)),
