@@ -178,6 +178,14 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
             constexpr int cur = decltype(PAR)::value;
             wait_vmcnt<LPS * (ST - 2)>();       // this wave's loads of step + 1 have landed
             __syncthreads();                    // ... everyone's have, and nobody reads the slot of `step` any more
+            // The slot of `step` is refilled by half of the waves before their MFMAs and by the other half after
+            // theirs: a wave is held while it issues its loads, and the two waves of a SIMD (w and w + WAVES / 2)
+            // then take turns at the matrix pipe instead of both issuing loads at the same time.
+            const bool early = WAVES >= 8 && wave < WAVES / 2;
+            if (early) {
+                issue(nxt == 0 ? ST - 1 : nxt - 1, step + ST < steps);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             read_stage(nxt, StepTag<cur ^ 1>{});
 #pragma unroll
             for (int kk = 0; kk < KI; ++kk)
@@ -192,7 +200,7 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
                 __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);    // LDS reads of the next step
             }
             __builtin_amdgcn_sched_barrier(0);
-            issue(nxt == 0 ? ST - 1 : nxt - 1, step + ST < steps);     // refill the slot of `step`
+            if (!early) issue(nxt == 0 ? ST - 1 : nxt - 1, step + ST < steps);     // refill the slot of `step`
             nxt = nxt + 1 == ST ? 0 : nxt + 1;
         };
         for (int step = 0; step < steps;) {
