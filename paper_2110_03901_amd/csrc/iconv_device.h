@@ -107,7 +107,10 @@ template <> __device__ __forceinline__ void store4<f16_t>(f16_t* p, float a, flo
 // back all at once, which is what 1.5-2.5 us at the end of every launch of the write-heavy layers consisted of.
 // Written through, they leave while the kernel still runs (measured: 3x3 64->64 layer -15 %, 1x1 256->512 -16 %,
 // 7x7 first layer -12 %, strided 3x3 -7 %, dilated 3x3 -5 %, 7x7-map 3x3 -3 %; sc0, nt and their combinations with
-// sc1 are no better, nt alone makes the first layer 14 % slower).
+// sc1 are no better, nt alone makes the first layer 14 % slower).  It pays only for stores that cover whole 128-byte
+// lines per instruction, which the staged epilogues do: written through in 8-byte pieces per lane a plain copy runs
+// at 2.5 instead of 5.8 TB/s, so the stores through plain pointers (odd filter counts, the lowering kernels, the copy
+// probe) keep the default policy.
 constexpr int kStoreYPolicy = 16;
 
 // Four consecutive fp32 results (one 16-byte staging piece) to a buffer, converted to the output
