@@ -541,13 +541,13 @@ bool pointwise_supported(const ConvShape& s) {
 }
 
 // Where these kernels measured faster than the per-tap kernels (28x28 and 56x56 maps, 64 to 256 channels, 128 to
-// 1024 filters, batch 16 to 128).  The MFMAs always run on 128 rows and every workgroup streams all filters, so a
-// workgroup needs enough pixels: 96 of 128 for the first form, 64 for the form with store waves, which loses less
-// when the tile is not full (its stores, not its MFMAs, set the pace).  With 128 or 256 channels the form with
-// store waves is the faster of the two (-3 to -12 %) unless a workgroup writes only four tiles and there are
-// several rounds of workgroups; at 64 channels three workgroups of the first form share a compute unit, which
-// overlaps as much.  With 256 channels a workgroup fills the LDS of a compute unit, and in several rounds the
-// per-tap kernel with 256 x 256 tiles is faster up to 256 filters.
+// 1024 filters, batch 16 to 128, with the output stores written through).  The MFMAs always run on 128 rows and
+// every workgroup streams all filters, so a workgroup needs enough pixels: 96 of 128 for the first form, 64 (48 at
+// 128 channels) for the form with store waves, which loses less when the tile is not full (its stores, not its
+// MFMAs, set the pace).  At 64 channels three workgroups of the first form share a compute unit, at 128 channels
+// two, and that overlaps as well as store waves do up to 512 filters; beyond, and at 256 channels (one workgroup
+// per compute unit either way), the store waves win (-3 to -12 %).  With 256 channels in several rounds of
+// workgroups the per-tap kernel with 256-row tiles is faster up to 256 filters.
 // Returns the variant (0: compute waves store, 1: store waves) or -1.
 int pointwise_choose(const ConvShape& s) {
     PwGeom g;
@@ -555,9 +555,12 @@ int pointwise_choose(const ConvShape& s) {
     const long nwg = (s.M + g.rows_per_wg - 1) / g.rows_per_wg;
     const bool one_round = nwg <= device_cus();
     if (s.C == 64) return g.rows_per_wg >= 96 ? 0 : -1;
+    if (s.C == 128) {
+        if (g.rows_per_wg < 48) return -1;
+        return g.rows_per_wg >= 96 && s.K <= 512 ? 0 : 1;
+    }
     if (g.rows_per_wg < 64) return -1;
     if (one_round) return 1;
-    if (s.C == 128) return s.K >= 256 ? 1 : (g.rows_per_wg >= 96 ? 0 : -1);
     return s.K >= 512 ? 1 : -1;
 }
 

@@ -724,12 +724,14 @@ bool stem_variant_supported(const ConvShape& s, int v) {
     if (!plan_stem(s, &g)) return false;
     return v == 0 || (v == 1 && stem_sw_fits(s, g));
 }
-// The form with store waves is the faster one (-6 % at 3 blocks per compute unit, -7 % at 6 and 12) once every
-// compute unit has a few blocks to pipeline; with 1.5 blocks per compute unit it is 4 % slower.
+// The form with store waves is the faster one (-7 to -15 % from two blocks per compute unit on, -10 % with at most one
+// block per compute unit) except between one and two blocks per compute unit, where half of its workgroups have
+// two blocks and the others wait (1.5 blocks per compute unit: +6 %).
 int stem_choose(const ConvShape& s) {
     StemGeom g;
     if (!plan_stem(s, &g)) return -1;
-    return stem_sw_fits(s, g) && g.total_tiles >= 3L * device_cus() ? 1 : 0;
+    const long cus = device_cus();
+    return stem_sw_fits(s, g) && (g.total_tiles <= cus || g.total_tiles >= 2 * cus) ? 1 : 0;
 }
 
 hipError_t launch_stem(const void* x, const void* w, void* y, const ConvShape& s, int in_t, int out_t, int v, hipStream_t st) {

@@ -146,6 +146,7 @@ def test_kernel_choice_follows_the_layer_class(lib):
     assert kernel_for(lib, 96, 7, 7, 512, 512, 3, 3, 1, 1, 1, bf16) == "p64x128_c128_w32x64_s3_4+4"    # 384 tiles: more than one round
     assert kernel_for(lib, 64, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem_8+4"           # 12 blocks per compute unit: store waves
     assert kernel_for(lib, 8, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem"                # 1.5 blocks per compute unit
+    assert kernel_for(lib, 4, 224, 224, 4, 64, 7, 7, 2, 3, 1, bf16) == "stem_8+4"            # at most one block per compute unit
     assert kernel_for(lib, 64, 224, 224, 4, 62, 7, 7, 2, 3, 1, bf16) == "stem"               # K % 4 != 0
     assert kernel_for(lib, 1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 0) == "direct"            # fp32
     assert kernel_for(lib, 2, 8, 8, 20, 16, 3, 3, 1, 1, 1, bf16) == "direct"         # C % 8 != 0
@@ -162,7 +163,9 @@ def test_kernel_choice_follows_the_layer_class(lib):
     assert kernel_for(lib, 16, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16).startswith("d")
     assert kernel_for(lib, 24, 56, 56, 256, 512, 1, 1, 2, 0, 1, bf16) == "a128x32_2x4+4+4"
     assert kernel_for(lib, 32, 56, 56, 64, 256, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+8"       # 64 channels: several per compute unit
-    assert kernel_for(lib, 32, 28, 28, 128, 512, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+4+4"    # 16 filter tiles per workgroup: store waves
+    assert kernel_for(lib, 32, 28, 28, 128, 1024, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+4+4"   # 128 channels, 32 filter tiles per workgroup: store waves
+    assert kernel_for(lib, 32, 28, 28, 128, 512, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+8"      # ... 16 tiles: two workgroups per compute unit overlap as well
+    assert kernel_for(lib, 24, 28, 28, 128, 256, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+4+4"    # 74 pixels per workgroup
     assert kernel_for(lib, 32, 56, 56, 128, 128, 1, 1, 1, 0, 1, bf16) == "a128x32_2x4+8"      # four tiles: the compute waves store
     assert kernel_for(lib, 32, 7, 7, 2048, 512, 1, 1, 1, 0, 1, bf16).startswith("d64x64")     # 1568 output pixels
     for args in [(3, 17, 19, 8, 8, 1, 1, 1, 0, 1, 2), (5, 9, 33, 48, 24, 5, 3, 2, 2, 1, 3), (1, 1, 1, 8, 1, 1, 1, 1, 0, 1, 4),
