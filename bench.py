@@ -317,6 +317,8 @@ def main():
         a = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
         b = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
         t_c = time_steps(lambda: B.iconv_probe_copy(b, a, nb), 20, 3, keep_busy=True)
+        # the same copy with the epilogues' store instructions (whole lines, written through)
+        t_cw = time_steps(lambda: B.iconv_probe_copy_wt(b, a, nb), 20, 3, keep_busy=True)
         # launch-to-launch period of graph nodes that do next to nothing (a 16-byte copy): the part of every
         # ms_per_step above that lies between kernels
         t_gap = time_steps(lambda: B.iconv_probe_copy(b, a, 16), 500, 20, keep_busy=True)
@@ -330,6 +332,7 @@ def main():
                              "mfma_frac_of_datasheet": round(probe_tflops / PEAK_MFMA_TFLOPS, 4),
                              "mfma_bf16_tflops_random_operands": round(probe_random, 1),
                              "copy_gbs_read_plus_write": round(2 * nb / (t_c * 1e-3) / 1e9, 1),
+                             "copy_gbs_write_through_stores": round(2 * nb / (t_cw * 1e-3) / 1e9, 1),
                              "value_frac_of_achievable_mfma": round(tflops / probe_tflops, 4),
                              "lds_cycles_per_b128_instruction_per_cu": lds_cost,
                              "graph_node_period_us_empty_kernel": round(t_gap * 1e3, 3),

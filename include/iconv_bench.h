@@ -51,6 +51,11 @@ int iconv_variant_accepts(int variant, int N, int H, int W, int C, int K, int R,
  * memory-traffic counters and to measure the achievable copy bandwidth. */
 int iconv_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* The same copy with the store instructions of the convolution kernels' epilogues (whole 128-byte lines per
+ * instruction, written through at system scope): the achievable read + write bandwidth for data that is
+ * written once.  bytes < 2^32 (ICONV_ERR_UNSUPPORTED otherwise); other errors as iconv_probe_copy. */
+int iconv_probe_copy_wt(void *dst, const void *src, size_t bytes, void *stream);
+
 /* A register-only loop of `iters` x 8 bf16 32x32x16 MFMAs per wave on 1024 workgroups of four
  * waves (no memory traffic in the loop), for the achievable matrix-core rate:
  * 1024 * 4 * iters * 8 * 32768 flop per launch.  random_operands = 0 multiplies one fixed pair of

@@ -45,6 +45,8 @@ _lib.iconv_im2col.restype = _i
 _lib.iconv_im2col.argtypes = [_p, _p, _sz] + [_i] * 10 + [_p]
 _lib.iconv_probe_copy.restype = _i
 _lib.iconv_probe_copy.argtypes = [_p, _p, _sz, _p]
+_lib.iconv_probe_copy_wt.restype = _i
+_lib.iconv_probe_copy_wt.argtypes = [_p, _p, _sz, _p]
 _lib.iconv_probe_mfma.restype = _i
 _lib.iconv_probe_mfma.argtypes = [_p, _sz, _i, _i, _p]
 _lib.iconv_probe_lds.restype = _i
@@ -70,7 +72,7 @@ NOALLOC_WORKSPACE_BYTES = 16 << 20
 EXPORTS = ["iconv_out_shape", "iconv_fwd", "iconv_fwd_channel_last", "iconv_workspace_bytes", "iconv_fwd_explicit",
            "iconv_fwd_explicit_noalloc", "iconv_im2col",
            "iconv_kernel_for", "iconv_status_string"]
-EXPORTS_BENCH = ["iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy", "iconv_probe_mfma", "iconv_probe_lds", "iconv_lds_swizzle", "iconv_lds_stage_offset"]
+EXPORTS_BENCH = ["iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy", "iconv_probe_copy_wt", "iconv_probe_mfma", "iconv_probe_lds", "iconv_lds_swizzle", "iconv_lds_stage_offset"]
 
 
 class IconvError(RuntimeError):
@@ -176,6 +178,12 @@ def iconv_im2col(x, workspace, workspace_bytes, N, H, W, C, R, S, stride, pad, d
 
 def iconv_probe_copy(dst, src, nbytes, stream=None) -> None:
     rc = _lib.iconv_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream))
+    if rc != 0:
+        raise IconvError(rc)
+
+
+def iconv_probe_copy_wt(dst, src, nbytes, stream=None) -> None:
+    rc = _lib.iconv_probe_copy_wt(_ptr(dst), _ptr(src), nbytes, _stream(stream))
     if rc != 0:
         raise IconvError(rc)
 

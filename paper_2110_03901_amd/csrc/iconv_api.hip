@@ -269,7 +269,16 @@ int iconv_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (bytes == 0 || (bytes & 15u)) return ICONV_ERR_SHAPE;
     if (!aligned16(dst) || !aligned16(src)) return ICONV_ERR_ALIGN;
     drop_stale_error();
-    return status_of(launch_copy(dst, src, bytes, (hipStream_t)stream));
+    return status_of(launch_copy(dst, src, bytes, (hipStream_t)stream, false));
+}
+
+int iconv_probe_copy_wt(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src) return ICONV_ERR_NULL;
+    if (bytes == 0 || (bytes & 15u)) return ICONV_ERR_SHAPE;
+    if (bytes >= (1ull << 32)) return ICONV_ERR_UNSUPPORTED;
+    if (!aligned16(dst) || !aligned16(src)) return ICONV_ERR_ALIGN;
+    drop_stale_error();
+    return status_of(launch_copy(dst, src, bytes, (hipStream_t)stream, true));
 }
 
 int iconv_probe_mfma(void* out, size_t out_bytes, int iters, int random_operands, void* stream) {

@@ -114,7 +114,7 @@ hipError_t launch_channel_last(const void* x_nchw, const void* w_kcrs, void* y, 
 // lowered matrix with rows of `pitch_elems` elements (>= Kg, zero tail); 16-bit filter rows copied to a padded pitch
 hipError_t launch_im2col(const void* x, void* lowered, const ConvShape& s, int elt_bytes, int pitch_elems, hipStream_t stream);
 hipError_t launch_pad_rows(const void* src, void* dst, int rows, int len, int pitch, hipStream_t stream);
-hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream, bool write_through);
 constexpr int kMfmaProbeGroups = 1024;   // workgroups of the MFMA probe (four per compute unit)
 hipError_t launch_mfma_probe(void* out, int iters, bool random_operands, hipStream_t stream);
 constexpr int kLdsProbePatterns = 8;

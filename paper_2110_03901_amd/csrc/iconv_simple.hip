@@ -119,6 +119,17 @@ __global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride_t) dst[i] = src[i];
 }
 
+// The same copy with the stores of the convolution kernels' epilogues: whole lines per instruction, written through
+// (kStoreYPolicy).  For destinations below 4 GiB (one buffer descriptor).
+__global__ void __launch_bounds__(256) copy_wt_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, uint32_t n16) {
+    const rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, n16 * 16u, kRsrcFlags);
+    const uint32_t stride_t = gridDim.x * blockDim.x;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride_t) {
+        const uint4 v = src[i];
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{v.x, v.y, v.z, v.w}, d_rsrc, (int)(i * 16u), 0, kStoreYPolicy);
+    }
+}
+
 // Register-only MFMA loop: eight independent accumulator tiles per wave, operands never reloaded.
 // RANDOM = false: one small-integer operand pair for all MFMAs (few bits toggle between
 // instructions); RANDOM = true: four operand pairs of pseudo-random values in +-[0.5, 1), a
@@ -333,10 +344,15 @@ int lds_swizzle(int chunks_per_row, int row, int chunk) {
     }
 }
 
-hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st, bool write_through) {
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(copy_kernel, dim3(grid_for((long long)n16, 256)), dim3(256), 0, st, (const uint4*)src,
-                       (uint4*)dst, n16);
+    if (write_through && bytes < (1ull << 32)) {
+        hipLaunchKernelGGL(copy_wt_kernel, dim3(grid_for((long long)n16, 256)), dim3(256), 0, st, (const uint4*)src,
+                           (uint4*)dst, (uint32_t)n16);
+    } else {
+        hipLaunchKernelGGL(copy_kernel, dim3(grid_for((long long)n16, 256)), dim3(256), 0, st, (const uint4*)src,
+                           (uint4*)dst, n16);
+    }
     return hipGetLastError();
 }
 

@@ -32,7 +32,7 @@ def test_header_symbols_exported(lib):
     assert {"iconv_fwd", "iconv_out_shape", "iconv_workspace_bytes", "iconv_fwd_explicit", "iconv_status_string"} <= set(names)
     bench = declared_functions(HEADER_BENCH)
     assert {"iconv_fwd_ex", "iconv_num_variants", "iconv_variant_name", "iconv_variant_accepts", "iconv_probe_copy",
-            "iconv_probe_mfma", "iconv_probe_lds", "iconv_lds_swizzle", "iconv_lds_stage_offset"} == set(bench)
+            "iconv_probe_copy_wt", "iconv_probe_mfma", "iconv_probe_lds", "iconv_lds_swizzle", "iconv_lds_stage_offset"} == set(bench)
     for n in names + bench:
         assert hasattr(lib, n), f"{n} is declared in a header but not exported"
 

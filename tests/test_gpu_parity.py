@@ -485,6 +485,10 @@ def test_probes_run_and_are_exact(B):
     B.iconv_probe_copy(dst, src, n)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+    dst.zero_()
+    B.iconv_probe_copy_wt(dst, src, n - 16 * 3)       # the variant with the epilogues' store instructions; a ragged last block
+    torch.cuda.synchronize()
+    assert torch.equal(src[:n - 48], dst[:n - 48]) and int(dst[n - 48:].sum()) == 0
     out = torch.full((B.MFMA_PROBE_GROUPS * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
     B.iconv_probe_mfma(out, out.numel() * 4, 1)
     torch.cuda.synchronize()
