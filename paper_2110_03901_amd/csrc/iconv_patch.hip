@@ -407,6 +407,16 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         for (int kk = 0; kk < KI; ++kk) b_idx[ni][kk] = row * CPR + swz<CPR>(row, kk * 2 + fk);
     }
     const bool vec_ok = (s.K & 3) == 0;
+    // Byte address of the lane's 16 bytes of patch pixel pp for K slice 0: window pp / PPW (256 bytes, so the window
+    // part of the address is a multiple of 256 and the slot part stays below 16), slot
+    // ((pp % PPW)*CPR + l/32) ^ (window & wmask).  K slice kk is the slot xor 2*kk, i.e. the byte address xor (kk << 5):
+    // one instruction per operand read.
+    const char* lds_c = reinterpret_cast<const char*>(lds);
+    auto operand_byte = [&](uint32_t patch_cur, uint32_t pp) __attribute__((always_inline)) {
+        const uint32_t win = pp / (uint32_t)PPW;
+        const uint32_t slot = ((pp % (uint32_t)PPW) * CPR + (uint32_t)fk) ^ (win & (uint32_t)wmask);
+        return (patch_cur + win * 16u + slot) << 4;
+    };
 
     // Epilogue of one tile for the fragments this wave owns.  The filter fragment is the MFMA's row
     // operand and the pixel fragment its column operand, so lane l holds block pixel 32*frag + l%32
@@ -513,7 +523,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
         constexpr int KG = KI / KPG;                // groups per step
         // read cursor: the step whose operands are fetched next
         int r_stage = 0, r_phase = 0, r_tr = 0, r_ts = 0;
-        int a_win[MI], a_sx[MI];
+        uint32_t a_byte[MI];                        // byte address of the step's pixel-fragment operand, K slice 0
         const u32x4* Bt = lds;
         auto point = [&]() __attribute__((always_inline)) {                        // operand addresses of the cursor's step
             const uint32_t patch_cur = (uint32_t)(r_phase & 1) * (g.patch_bytes >> 4);
@@ -521,9 +531,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
             Bt = lds + ((bstage_off + r_stage * BSTAGE_BYTES) >> 4);
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                const int pp = a_base[mi] + tap_off;
-                a_win[mi] = patch_cur + (pp / PPW) * 16;
-                a_sx[mi] = ((pp % PPW) * CPR + fk) ^ ((pp / PPW) & wmask);
+                a_byte[mi] = operand_byte(patch_cur, (uint32_t)(a_base[mi] + tap_off));
             }
         };
         auto advance = [&]() __attribute__((always_inline)) {      // branch-free: the step stays one scheduling region
@@ -544,7 +552,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 constexpr int j0 = gk * KPG;
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    af[buf][k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ ((j0 + k2) * 2))]);
+                    af[buf][k2][mi] = *reinterpret_cast<const frag_t*>(lds_c + (a_byte[mi] ^ (uint32_t)((j0 + k2) << 5)));
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) bfr[buf][k2][ni] = __builtin_bit_cast(frag_t, Bt[b_idx[ni][j0 + k2]]);
             }
@@ -642,13 +650,9 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                 __syncthreads();                // this step's filter tile (and patch) has landed
                 const int tap_off = (tap_r * g.PW + tap_s) * s.dil;
                 const u32x4* Bt = lds + ((bstage_off + stage * BSTAGE_BYTES) >> 4);
-                int a_win[MI], a_sx[MI];
+                uint32_t a_byte[MI];
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    const int pp = a_base[mi] + tap_off;
-                    a_win[mi] = patch_cur + (pp / PPW) * 16;          // 256-byte window of this pixel
-                    a_sx[mi] = ((pp % PPW) * CPR + fk) ^ ((pp / PPW) & wmask);
-                }
+                for (int mi = 0; mi < MI; ++mi) a_byte[mi] = operand_byte(patch_cur, (uint32_t)(a_base[mi] + tap_off));
                 // operand fragments LDS -> registers and MFMAs, in KG groups of K slices: all reads of
                 // a group are issued before its first MFMA, and the next group's reads follow that
                 // group's MFMAs into the pipe
@@ -664,7 +668,7 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
                         const int kk = gk * KPG + k2;
 #pragma unroll
                         for (int mi = 0; mi < MI; ++mi)
-                            af[k2][mi] = __builtin_bit_cast(frag_t, lds[a_win[mi] + (a_sx[mi] ^ (kk * 2))]);
+                            af[k2][mi] = *reinterpret_cast<const frag_t*>(lds_c + (a_byte[mi] ^ (uint32_t)(kk << 5)));
 #pragma unroll
                         for (int ni = 0; ni < NI; ++ni) bfr[k2][ni] = __builtin_bit_cast(frag_t, Bt[b_idx[ni][kk]]);
                     }
