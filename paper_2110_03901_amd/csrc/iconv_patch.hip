@@ -590,17 +590,10 @@ ipatch_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restrict__
 #pragma unroll
                             for (int ni = 0; ni < NI; ++ni)
                                 acc[mi][ni] = Elem<T>::mfma32(bfr[cur][k2][ni], af[cur][k2][mi], acc[mi][ni]);
-                    // Issue order within the group: one MFMA, then the address arithmetic and LDS reads
-                    // of the next group that fit into the 32 cycles the matrix pipe works on it.  A wave
-                    // issues in order, so only instructions placed BETWEEN its MFMAs overlap with them.
-                    constexpr int NM = KPG * MI * NI, NR = KPG * (MI + NI);
-                    constexpr int RPM = (NR + NM - 1) / NM;
-#pragma unroll
-                    for (int i = 0; i < NM; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);      // VALU
-                        __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);    // LDS read
-                    }
+                    // A wave issues in order, so only instructions placed BETWEEN its MFMAs overlap with them.  The
+                    // compiler's own interleaving of the next group's address arithmetic and LDS reads with this
+                    // group's MFMAs measured 2-3 % faster than recipes of the form "one MFMA, n vector instructions,
+                    // one LDS read" (n = 2, 3, 6, 8), so the order within a step is left to it.
                 };
                 body(IntTag<0>{});
                 if constexpr (KG > 1) body(IntTag<1>{});
