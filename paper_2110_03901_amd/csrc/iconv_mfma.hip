@@ -197,6 +197,7 @@ igemm_dma_kernel(const T* __restrict__ x, const T* __restrict__ w, TO* __restric
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);      // address arithmetic of the reads (measured: -1 % against none, 1 or 4)
                 __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);    // LDS reads of the next step
             }
             __builtin_amdgcn_sched_barrier(0);
