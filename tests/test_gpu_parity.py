@@ -739,3 +739,44 @@ def test_random_shapes_through_the_default_choice_and_forced_kernels(B):
         for v in forced:
             print("shape", dims, "variant", names[v] if v >= 0 else "auto", flush=True)
             check(B, L, variant=v)
+
+
+def _random_wide_shapes(count, seed):
+    """Layers with the channel and filter counts the specialised kernels take (64 ... 512 channels, 128-channel
+    steps, K split, pixel-resident 1x1 forms), small enough for the oracle."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 1, 3, 3, 3, 5])); S = R if rng.random() < 0.8 else int(rng.choice([1, 3]))
+        stride = int(rng.choice([1, 1, 1, 2, 2, 3])); dil = int(rng.choice([1, 1, 1, 2, 3])); pad = int(rng.integers(0, 5))
+        C = int(rng.choice([32, 64, 64, 96, 128, 128, 192, 256, 320, 512])); K = int(rng.choice([32, 62, 64, 96, 128, 136, 256, 300, 512]))
+        N = int(rng.integers(1, 6)); H = int(rng.integers(5, 35)); W = H if rng.random() < 0.5 else int(rng.integers(5, 35))
+        if H + 2 * pad - dil * (R - 1) - 1 < 0 or W + 2 * pad - dil * (S - 1) - 1 < 0:
+            continue
+        P = (H + 2 * pad - dil * (R - 1) - 1) // stride + 1
+        Q = (W + 2 * pad - dil * (S - 1) - 1) // stride + 1
+        if N * P * Q * K * C * R * S > 1.5e9:
+            continue
+        out.append((N, H, W, C, K, R, S, stride, pad, dil))
+    return out
+
+
+def test_random_wide_layers_through_every_kernel_that_accepts_them(B):
+    """Seeded random layers with many channels and filters through the library's own choice and through every
+    kernel-table entry that accepts them, each also with its workgroups capped at three (several tiles or
+    blocks per workgroup, ragged last workgroup)."""
+    names = variant_names(B)
+    ran = 0
+    for i, dims in enumerate(_random_wide_shapes(40, 20212)):
+        L = workloads.small_layer(f"wide{i}", *dims, dtype="bf16" if i % 2 == 0 else "f16", seed_id=800 + i)
+        x, w = workloads.make_inputs(L)
+        ref = conv_ref(x, w, L.stride, L.pad, L.dilation)
+        code = code_of(L)
+        cases = [(-1, 0)] + [(v, cap) for v in range(len(names)) if B.iconv_variant_accepts(v, *L.shape_args(), code)
+                             for cap in (0, 3)]
+        for v, cap in cases:
+            print("shape", dims, L.dtype, "variant", names[v] if v >= 0 else "auto", "cap", cap, flush=True)
+            err = rel_err(run_gpu(B, L, x, w, code, variant=v, cap=cap), ref)
+            assert err <= TIGHT, (dims, names[v] if v >= 0 else "auto", cap, err)
+            ran += 1
+    assert ran >= 40 * 5
